@@ -1,0 +1,196 @@
+"""Thin ctypes binding of libduplexkv.so: same names as include/duplexkv.h,
+argument marshalling only.  Every byte is moved by the library's HIP code;
+there is no fallback: if the library is missing, importing this fails loudly."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+# PyTorch ships its own HIP runtime.  It must be in the process before this
+# library is loaded so that both resolve to the same libamdhip64 (two runtimes
+# in one process do not see the device); torch also owns the cache allocation.
+import torch  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libduplexkv.so")
+
+KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP = \
+    0, -1, -2, -3, -4, -5, -6, -7
+KV_HOST_BLOCK_FIRST, KV_HOST_LAYER_FIRST = 0, 1
+KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSED = 0, 1, 2, 3, 4
+PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"}
+
+EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
+           "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
+           "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_strerror"]
+
+
+class kv_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes", "n_hbm_blocks",
+        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "reserved")] + \
+        [("staging_bytes", C.c_uint64)]
+
+
+class kv_stats(C.Structure):
+    _fields_ = [("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("ms_out", C.c_double),
+                ("ms_in", C.c_double), ("ms_e2e", C.c_double), ("path_used", C.c_int32),
+                ("n_launches", C.c_int32)]
+
+
+class KVError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {kv_strerror(code)} ({code})")
+        self.code = code
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -m paper_2601_20309_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    p32, pcfg = C.POINTER(C.c_int32), C.POINTER(kv_config)
+    for n in ("kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes"):
+        getattr(L, n).restype = C.c_uint64
+        getattr(L, n).argtypes = [pcfg]
+    L.kv_validate.restype = C.c_int
+    L.kv_validate.argtypes = [pcfg, p32, p32, C.c_int32, p32, p32, C.c_int32]
+    L.kv_create.restype = C.c_int
+    L.kv_create.argtypes = [C.POINTER(C.c_void_p), pcfg, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.kv_destroy.restype = C.c_int
+    L.kv_destroy.argtypes = [C.c_void_p]
+    L.kv_swap_out.restype = C.c_int
+    L.kv_swap_out.argtypes = [C.c_void_p, p32, p32, C.c_int32]
+    L.kv_swap_in.restype = C.c_int
+    L.kv_swap_in.argtypes = [C.c_void_p, p32, p32, C.c_int32]
+    L.kv_rotate.restype = C.c_int
+    L.kv_rotate.argtypes = [C.c_void_p, p32, p32, C.c_int32, p32, p32, C.c_int32]
+    L.kv_wait.restype = C.c_int
+    L.kv_wait.argtypes = [C.c_void_p]
+    L.kv_host_pool.restype = C.c_int
+    L.kv_host_pool.argtypes = [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_uint64)]
+    L.kv_last_stats.restype = C.c_int
+    L.kv_last_stats.argtypes = [C.c_void_p, C.POINTER(kv_stats)]
+    L.kv_probe_link.restype = C.c_int
+    L.kv_probe_link.argtypes = [C.c_uint64, C.c_int32] + [C.POINTER(C.c_double)] * 4
+    L.kv_strerror.restype = C.c_char_p
+    L.kv_strerror.argtypes = [C.c_int]
+    return L
+
+
+lib = _load()
+
+
+def make_config(shape, host_layout=KV_HOST_BLOCK_FIRST, path=KV_PATH_AUTO, chunk_layers=0,
+                max_copy_wgs=0, staging_bytes=0) -> kv_config:
+    """kv_config from any object carrying the KV shape attributes."""
+    return kv_config(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
+                     shape.elem_bytes, shape.n_hbm_blocks, shape.n_host_slots, host_layout, path,
+                     chunk_layers, max_copy_wgs, 0, staging_bytes)
+
+
+def _ids(a):
+    if a is None:
+        return None, 0, None
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    if arr.size == 0:
+        return None, 0, arr
+    return arr.ctypes.data_as(C.POINTER(C.c_int32)), int(arr.size), arr
+
+
+def kv_strerror(code: int) -> str:
+    return lib.kv_strerror(code).decode()
+
+
+def kv_seg_bytes(cfg): return int(lib.kv_seg_bytes(C.byref(cfg)))
+def kv_block_bytes(cfg): return int(lib.kv_block_bytes(C.byref(cfg)))
+def kv_cache_bytes(cfg): return int(lib.kv_cache_bytes(C.byref(cfg)))
+def kv_pool_bytes(cfg): return int(lib.kv_pool_bytes(C.byref(cfg)))
+
+
+def kv_validate(cfg, out_block_ids, out_host_slots, in_block_ids, in_host_slots,
+                n_out: Optional[int] = None, n_in: Optional[int] = None) -> int:
+    po, no, k1 = _ids(out_block_ids); ps, no2, k2 = _ids(out_host_slots)
+    pi, ni, k3 = _ids(in_block_ids); pis, ni2, k4 = _ids(in_host_slots)
+    assert no == no2 and ni == ni2
+    return lib.kv_validate(C.byref(cfg), po, ps, no if n_out is None else n_out,
+                           pi, pis, ni if n_in is None else n_in)
+
+
+def kv_probe_link(nbytes: int, reps: int = 5) -> dict:
+    v = [C.c_double() for _ in range(4)]
+    rc = lib.kv_probe_link(nbytes, reps, *[C.byref(x) for x in v])
+    if rc != KV_OK:
+        raise KVError(rc, "kv_probe_link")
+    return dict(d2h=v[0].value, h2d=v[1].value, d2h_duplex=v[2].value, h2d_duplex=v[3].value)
+
+
+class Engine:
+    """Owns one kv_engine handle.  Methods carry the C names and return the C
+    result code (raise_on_error=False) or raise KVError."""
+
+    def __init__(self, cfg: kv_config, hbm_cache_ptr: int, host_pool_ptr: int = 0,
+                 stream_out: int = 0, stream_in: int = 0):
+        self.cfg = cfg
+        self._h = C.c_void_p()
+        rc = lib.kv_create(C.byref(self._h), C.byref(cfg), C.c_void_p(hbm_cache_ptr),
+                           C.c_void_p(host_pool_ptr or None), C.c_void_p(stream_out or None),
+                           C.c_void_p(stream_in or None))
+        if rc != KV_OK:
+            self._h = C.c_void_p()
+            raise KVError(rc, "kv_create")
+
+    def kv_swap_out(self, block_ids, host_slots) -> int:
+        pi, n, k1 = _ids(block_ids); ps, n2, k2 = _ids(host_slots)
+        assert n == n2
+        return lib.kv_swap_out(self._h, pi, ps, n)
+
+    def kv_swap_in(self, host_slots, block_ids) -> int:
+        ps, n, k1 = _ids(host_slots); pi, n2, k2 = _ids(block_ids)
+        assert n == n2
+        return lib.kv_swap_in(self._h, ps, pi, n)
+
+    def kv_rotate(self, out_block_ids, out_host_slots, in_block_ids, in_host_slots) -> int:
+        po, no, k1 = _ids(out_block_ids); ps, no2, k2 = _ids(out_host_slots)
+        pi, ni, k3 = _ids(in_block_ids); pis, ni2, k4 = _ids(in_host_slots)
+        assert no == no2 and ni == ni2
+        return lib.kv_rotate(self._h, po, ps, no, pi, pis, ni)
+
+    def kv_wait(self) -> int:
+        return lib.kv_wait(self._h)
+
+    def kv_host_pool(self):
+        ptr, n = C.c_void_p(), C.c_uint64()
+        rc = lib.kv_host_pool(self._h, C.byref(ptr), C.byref(n))
+        if rc != KV_OK:
+            raise KVError(rc, "kv_host_pool")
+        return ptr.value, n.value
+
+    def host_pool_array(self) -> np.ndarray:
+        """The pool as a uint8 NumPy array over the pinned memory (no copy)."""
+        ptr, n = self.kv_host_pool()
+        buf = (C.c_uint8 * n).from_address(ptr)
+        return np.frombuffer(buf, dtype=np.uint8)
+
+    def kv_last_stats(self) -> dict:
+        st = kv_stats()
+        rc = lib.kv_last_stats(self._h, C.byref(st))
+        if rc != KV_OK:
+            raise KVError(rc, "kv_last_stats")
+        return {f: getattr(st, f) for f, _ in kv_stats._fields_}
+
+    def kv_destroy(self) -> int:
+        if self._h:
+            rc = lib.kv_destroy(self._h)
+            self._h = C.c_void_p()
+            return rc
+        return KV_OK
+
+    def __del__(self):
+        try:
+            self.kv_destroy()
+        except Exception:
+            pass

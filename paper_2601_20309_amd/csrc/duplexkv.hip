@@ -1,0 +1,963 @@
+// Host side of the KV rotation engine and its C ABI (see include/duplexkv.h).
+//
+// Paths (how one call's bytes travel):
+//   FUSED        one kv_move_kernel launch carries both directions, each lane
+//                alternating an out-vector with an in-vector; zero-copy into /
+//                out of the pinned pool.  Default for kv_rotate.
+//   ZEROCOPY     the same kernel once per direction on the two streams.
+//                Default for kv_swap_out / kv_swap_in.
+//   SDMA_STAGED  pack kernel -> HBM staging -> hipMemcpyAsync per contiguous
+//                host run (DMA engines), and the mirror; chunks are double
+//                buffered so pack(c+1) overlaps copy(c) and copy(c+1) overlaps
+//                unpack(c).  Uses no compute units for the link itself.
+//   NAIVE        one hipMemcpyAsync per segment, the per-segment baseline of
+//                Section 4.3.1 of the paper, kept for the benchmark ladder.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/duplexkv.h"
+#include "kv_kernels.hpp"
+
+namespace {
+
+using dkv::DirDesc;
+using dkv::MoveParams;
+
+double now_ms()
+{
+    using clk = std::chrono::steady_clock;
+    return std::chrono::duration<double, std::milli>(clk::now().time_since_epoch()).count();
+}
+
+bool config_ok(const kv_config *c)
+{
+    if (!c) return false;
+    if (c->n_layers <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->block_size <= 0 ||
+        c->elem_bytes <= 0 || c->n_hbm_blocks <= 0 || c->n_host_slots <= 0)
+        return false;
+    if (c->host_layout != KV_HOST_BLOCK_FIRST && c->host_layout != KV_HOST_LAYER_FIRST) return false;
+    if (c->path < KV_PATH_AUTO || c->path > KV_PATH_FUSED) return false;
+    if (c->chunk_layers < 0 || c->max_copy_wgs < 0 || c->reserved != 0) return false;
+    // sizes must stay far inside 64 bits
+    const long double cache = 2.0L * c->n_layers * (long double)c->n_hbm_blocks * c->block_size *
+                              c->n_kv_heads * c->head_dim * c->elem_bytes;
+    const long double pool = 2.0L * c->n_layers * (long double)c->n_host_slots * c->block_size *
+                             c->n_kv_heads * c->head_dim * c->elem_bytes;
+    return cache < 1e18L && pool < 1e18L;
+}
+
+// ---- admission (host only) ------------------------------------------------
+// mark[] holds (epoch << 2) | bits, bits: 1 = named by the out list, 2 = by the in list.
+struct Marks {
+    std::vector<uint32_t> blk, slot;
+    uint32_t epoch = 0;
+    void reset(size_t nb, size_t ns) { blk.assign(nb, 0); slot.assign(ns, 0); epoch = 0; }
+    void next()
+    {
+        if (++epoch >= (1u << 30)) {
+            std::fill(blk.begin(), blk.end(), 0u);
+            std::fill(slot.begin(), slot.end(), 0u);
+            epoch = 1;
+        }
+    }
+};
+
+bool list_bad(const int32_t *p, int32_t n) { return n < 0 || (n > 0 && !p); }
+
+bool out_of_range(const int32_t *p, int32_t n, int32_t lim)
+{
+    for (int32_t i = 0; i < n; i++)
+        if (p[i] < 0 || p[i] >= lim) return true;
+    return false;
+}
+
+// Marks `p` with `bit`; reports a repeat inside this list and a hit on the other list.
+void mark_list(std::vector<uint32_t> &m, uint32_t epoch, const int32_t *p, int32_t n, uint32_t bit,
+               bool &dup, bool &overlap)
+{
+    for (int32_t i = 0; i < n; i++) {
+        uint32_t &w = m[(size_t)p[i]];
+        uint32_t bits = (w >> 2) == epoch ? (w & 3u) : 0u;
+        if (bits & bit) dup = true;
+        if (bits & ~bit) overlap = true;
+        w = (epoch << 2) | bits | bit;
+    }
+}
+
+int admit(const kv_config *c, Marks &mk, const int32_t *oi, const int32_t *os, int32_t no,
+          const int32_t *ii, const int32_t *is, int32_t ni)
+{
+    if (list_bad(oi, no) || list_bad(os, no) || list_bad(ii, ni) || list_bad(is, ni)) return KV_EINVAL;
+    if (out_of_range(oi, no, c->n_hbm_blocks) || out_of_range(ii, ni, c->n_hbm_blocks) ||
+        out_of_range(os, no, c->n_host_slots) || out_of_range(is, ni, c->n_host_slots))
+        return KV_ERANGE;
+    mk.next();
+    bool dup = false, overlap = false;
+    mark_list(mk.blk, mk.epoch, oi, no, 1u, dup, overlap);
+    mark_list(mk.blk, mk.epoch, ii, ni, 2u, dup, overlap);
+    mark_list(mk.slot, mk.epoch, os, no, 1u, dup, overlap);
+    mark_list(mk.slot, mk.epoch, is, ni, 2u, dup, overlap);
+    if (dup) return KV_EDUP;
+    if (overlap) return KV_EOVERLAP;
+    return KV_OK;
+}
+
+constexpr int kRing = 8;       // descriptor sets that may be in flight
+constexpr int kStageBufs = 2;  // double buffering of staging chunks
+
+struct StageDir {
+    uint8_t *buf[kStageBufs] = {nullptr, nullptr};
+    hipEvent_t kernel_done[kStageBufs] = {nullptr, nullptr};  // pack / unpack finished with buf
+    hipEvent_t copy_done[kStageBufs] = {nullptr, nullptr};    // DMA finished with buf
+    bool used[kStageBufs] = {false, false};
+    hipStream_t kstream = nullptr;                            // pack / unpack kernels
+};
+
+}  // namespace
+
+struct kv_engine {
+    kv_config cfg;
+    int device = 0;
+    uint64_t seg = 0, block_bytes = 0, cache_bytes = 0, pool_bytes = 0;
+    uint32_t n_planes = 0;
+    int vec = 1;  // bytes per lane access
+    uint8_t *hbm = nullptr;
+    uint8_t *pool = nullptr;
+    bool own_pool = false;
+    hipStream_t s_out = nullptr, s_in = nullptr;
+    bool own_streams = false;
+    int n_cus = 0;
+
+    // descriptor ring: per set [out_ids | out_slots | in_ids | in_slots]
+    int32_t *desc_host = nullptr, *desc_dev = nullptr;
+    size_t desc_cap = 0;  // ints per set
+    hipEvent_t ring_out[kRing] = {}, ring_in[kRing] = {};
+    bool ring_used[kRing] = {};
+    int ring_cur = 0;
+
+    Marks marks;
+    std::vector<std::pair<int32_t, int32_t>> sort_tmp;  // (slot, id)
+
+    // stats
+    hipEvent_t ev_o0 = nullptr, ev_o1 = nullptr, ev_i0 = nullptr, ev_i1 = nullptr, ev_join = nullptr,
+               ev_join2 = nullptr;
+    bool batch_open = false, have_o = false, have_i = false;
+    double t0 = 0;
+    kv_stats acc{}, last{};
+    int sticky = KV_OK;
+
+    // staging for SDMA_STAGED
+    StageDir st_out, st_in;
+    uint64_t chunk_cap = 0;
+};
+
+namespace {
+
+#define HIPTRY(e, call)                                                                      \
+    do {                                                                                     \
+        hipError_t err_ = (call);                                                            \
+        if (err_ != hipSuccess) {                                                            \
+            fprintf(stderr, "duplexkv: %s failed: %s (%s:%d)\n", #call, hipGetErrorString(err_), \
+                    __FILE__, __LINE__);                                                     \
+            if (e) (e)->sticky = KV_EHIP;                                                    \
+            return KV_EHIP;                                                                  \
+        }                                                                                    \
+    } while (0)
+
+uint64_t seg_of(const kv_config *c)
+{
+    return (uint64_t)c->block_size * (uint64_t)c->n_kv_heads * (uint64_t)c->head_dim *
+           (uint64_t)c->elem_bytes;
+}
+
+int pick_vec(const kv_engine *e)
+{
+    const uint64_t a = (uint64_t)(uintptr_t)e->hbm | (uint64_t)(uintptr_t)e->pool | e->seg;
+    for (int v = 16; v > 1; v >>= 1)
+        if ((a & (uint64_t)(v - 1)) == 0) return v;
+    return 1;
+}
+
+template <int U>
+void launch_move(int vec, int wgs, hipStream_t s, const MoveParams &p)
+{
+    dim3 g((unsigned)wgs), b(dkv::kThreads);
+    switch (vec) {
+    case 16: hipLaunchKernelGGL((dkv::kv_move_kernel<dkv::u32x4, U>), g, b, 0, s, p); break;
+    case 8: hipLaunchKernelGGL((dkv::kv_move_kernel<dkv::u32x2, U>), g, b, 0, s, p); break;
+    case 4: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned int, U>), g, b, 0, s, p); break;
+    case 2: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned short, U>), g, b, 0, s, p); break;
+    default: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned char, U>), g, b, 0, s, p); break;
+    }
+}
+
+// Fills the fields common to every launch; `u` = vectors per lane per tile.
+MoveParams base_params(const kv_engine *e, int u)
+{
+    MoveParams p{};
+    p.hbm = e->hbm;
+    p.seg_bytes = e->seg;
+    p.hbm_plane_stride = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    p.plane0 = 0;
+    p.n_planes = e->n_planes;
+    p.vec_per_seg = (uint32_t)(e->seg / (uint64_t)e->vec);
+    const uint32_t tile = (uint32_t)dkv::kThreads * (uint32_t)u;
+    p.tiles_per_seg = (p.vec_per_seg + tile - 1) / tile;
+    return p;
+}
+
+void pool_strides(const kv_engine *e, uint64_t &slot_stride, uint64_t &plane_stride)
+{
+    if (e->cfg.host_layout == KV_HOST_BLOCK_FIRST) {
+        slot_stride = (uint64_t)e->n_planes * e->seg;
+        plane_stride = e->seg;
+    } else {
+        slot_stride = e->seg;
+        plane_stride = (uint64_t)e->cfg.n_host_slots * e->seg;
+    }
+}
+
+// tiles of one direction over `planes` planes; false if it does not fit 32 bits
+bool dir_tiles(uint32_t n, uint32_t planes, uint32_t tiles_per_seg, uint32_t &tiles)
+{
+    const uint64_t t = (uint64_t)n * planes * tiles_per_seg;
+    if (t >= 0xFFFFFFFFull) return false;
+    tiles = (uint32_t)t;
+    return true;
+}
+
+int acquire_ring(kv_engine *e, int &k)
+{
+    k = e->ring_cur;
+    e->ring_cur = (e->ring_cur + 1) % kRing;
+    if (e->ring_used[k]) {  // set still referenced by enqueued work: let it drain
+        HIPTRY(e, hipEventSynchronize(e->ring_out[k]));
+        HIPTRY(e, hipEventSynchronize(e->ring_in[k]));
+    }
+    e->ring_used[k] = true;
+    return KV_OK;
+}
+
+void open_batch(kv_engine *e)
+{
+    if (!e->batch_open) {
+        e->batch_open = true;
+        e->have_o = e->have_i = false;
+        e->t0 = now_ms();
+        e->acc = kv_stats{};
+    }
+}
+
+int mark_start(kv_engine *e, bool out_side, hipStream_t s)
+{
+    if (out_side && !e->have_o) {
+        HIPTRY(e, hipEventRecord(e->ev_o0, s));
+        e->have_o = true;
+    }
+    if (!out_side && !e->have_i) {
+        HIPTRY(e, hipEventRecord(e->ev_i0, s));
+        e->have_i = true;
+    }
+    return KV_OK;
+}
+
+int default_wgs(const kv_engine *e, bool link_bound)
+{
+    // Link-bound launches need few workgroups: 128 x 256 lanes x 16 B keeps
+    // 512 KiB in flight per direction, enough to cover PCIe latency at 57 GB/s,
+    // while more only adds contention (measured).  HBM-bound pack / unpack
+    // launches want the whole chip.
+    int w = link_bound ? 128 : 8 * (e->n_cus > 0 ? e->n_cus : 256);
+    if (e->cfg.max_copy_wgs > 0) w = std::min(w, (int)e->cfg.max_copy_wgs);
+    return std::max(w, 1);
+}
+
+// ---- FUSED / ZEROCOPY -----------------------------------------------------
+int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
+{
+    int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
+    int32_t *dd = e->desc_dev + (size_t)k * e->desc_cap;
+    const int u = 1;
+    MoveParams p = base_params(e, u);
+    p.far_out = e->pool;
+    p.far_in = e->pool;
+    pool_strides(e, p.far_slot_stride_out, p.far_plane_stride_out);
+    p.far_slot_stride_in = p.far_slot_stride_out;
+    p.far_plane_stride_in = p.far_plane_stride_out;
+    p.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
+    DirDesc dout{dd, dd + no, (uint32_t)no, 0}, din{dd + 2 * (size_t)no, dd + 2 * (size_t)no + ni,
+                                                   (uint32_t)ni, 0};
+    if (!dir_tiles((uint32_t)no, p.n_planes, p.tiles_per_seg, dout.tiles) ||
+        !dir_tiles((uint32_t)ni, p.n_planes, p.tiles_per_seg, din.tiles))
+        return KV_EUNSUP;
+    const size_t ints_out = 2 * (size_t)no, ints_in = 2 * (size_t)ni;
+    const DirDesc none{nullptr, nullptr, 0, 0};
+
+    if (path == KV_PATH_FUSED && no > 0 && ni > 0) {
+        // one launch on stream_out; stream_in is joined before and after
+        HIPTRY(e, hipEventRecord(e->ev_join, e->s_in));
+        HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
+        HIPTRY(e, hipMemcpyAsync(dd, dh, (ints_out + ints_in) * sizeof(int32_t), hipMemcpyHostToDevice,
+                                 e->s_out));
+        if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
+        if (!e->have_i) {
+            e->have_i = true;
+            HIPTRY(e, hipEventRecord(e->ev_i0, e->s_out));
+        }
+        p.out = dout;
+        p.in = din;
+        const uint32_t tiles = std::max(dout.tiles, din.tiles);
+        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true), tiles);
+        launch_move<1>(e->vec, wgs, e->s_out, p);
+        HIPTRY(e, hipGetLastError());
+        HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
+        HIPTRY(e, hipEventRecord(e->ev_i1, e->s_out));
+        HIPTRY(e, hipEventRecord(e->ring_out[k], e->s_out));
+        HIPTRY(e, hipEventRecord(e->ring_in[k], e->s_out));
+        HIPTRY(e, hipEventRecord(e->ev_join2, e->s_out));
+        HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join2, 0));
+        e->acc.n_launches += 1;
+        return KV_OK;
+    }
+    // one kernel per direction, each on its own stream
+    if (no > 0) {
+        HIPTRY(e, hipMemcpyAsync(dd, dh, ints_out * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
+        if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
+        p.out = dout;
+        p.in = none;
+        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true), dout.tiles);
+        launch_move<1>(e->vec, wgs, e->s_out, p);
+        HIPTRY(e, hipGetLastError());
+        HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
+        e->acc.n_launches += 1;
+    }
+    if (ni > 0) {
+        HIPTRY(e, hipMemcpyAsync(dd + ints_out, dh + ints_out, ints_in * sizeof(int32_t),
+                                 hipMemcpyHostToDevice, e->s_in));
+        if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
+        p.out = none;
+        p.in = din;
+        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true), din.tiles);
+        launch_move<1>(e->vec, wgs, e->s_in, p);
+        HIPTRY(e, hipGetLastError());
+        HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
+        e->acc.n_launches += 1;
+    }
+    HIPTRY(e, hipEventRecord(e->ring_out[k], e->s_out));
+    HIPTRY(e, hipEventRecord(e->ring_in[k], e->s_in));
+    return KV_OK;
+}
+
+// ---- NAIVE: one copy per segment -------------------------------------------
+int run_naive(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+              const int32_t *is, int32_t ni)
+{
+    uint64_t ss, ps;
+    pool_strides(e, ss, ps);
+    const uint64_t hps = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    if (no > 0 && mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
+    if (ni > 0 && mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
+    const int32_t nmax = std::max(no, ni);
+    for (int32_t i = 0; i < nmax; i++) {  // interleave so both streams fill together
+        for (uint32_t pl = 0; pl < e->n_planes; pl++) {
+            if (i < no) {
+                HIPTRY(e, hipMemcpyAsync(e->pool + (uint64_t)os[i] * ss + pl * ps,
+                                         e->hbm + pl * hps + (uint64_t)oi[i] * e->seg, e->seg,
+                                         hipMemcpyDeviceToHost, e->s_out));
+            }
+            if (i < ni) {
+                HIPTRY(e, hipMemcpyAsync(e->hbm + pl * hps + (uint64_t)ii[i] * e->seg,
+                                         e->pool + (uint64_t)is[i] * ss + pl * ps, e->seg,
+                                         hipMemcpyHostToDevice, e->s_in));
+            }
+        }
+    }
+    e->acc.n_launches += (int32_t)(((int64_t)no + ni) * e->n_planes);
+    if (no > 0) HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
+    if (ni > 0) HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
+    return KV_OK;
+}
+
+// ---- SDMA_STAGED -----------------------------------------------------------
+// A chunk is blocks [j0, j1) of the slot-sorted list x planes [p0, p1).  Its
+// staging image mirrors the host layout ([j][plane][seg] for block-first,
+// [plane][j][seg] for layer-first) so that every run of consecutive slots is
+// one contiguous range on both sides and costs one DMA copy.
+struct ChunkPlan {
+    uint32_t blocks_per_chunk, planes_per_chunk;
+};
+
+int plan_chunks(const kv_engine *e, uint32_t n, ChunkPlan &pl)
+{
+    const uint64_t cap = e->chunk_cap;
+    if (e->cfg.host_layout == KV_HOST_BLOCK_FIRST) {
+        uint32_t planes = e->cfg.chunk_layers > 0 ? std::min<uint32_t>(2u * e->cfg.chunk_layers, e->n_planes)
+                                                 : e->n_planes;
+        while (planes > 2 && (uint64_t)planes * e->seg > cap) planes -= 2;
+        if ((uint64_t)planes * e->seg > cap) return KV_EUNSUP;
+        pl.planes_per_chunk = planes;
+        pl.blocks_per_chunk = (uint32_t)std::min<uint64_t>(n, cap / ((uint64_t)planes * e->seg));
+    } else {
+        uint32_t blocks = n;
+        if (2ull * blocks * e->seg > cap) blocks = (uint32_t)(cap / (2ull * e->seg));
+        if (blocks == 0) return KV_EUNSUP;
+        uint32_t layers = (uint32_t)std::min<uint64_t>((uint64_t)e->cfg.n_layers,
+                                                        cap / (2ull * blocks * e->seg));
+        if (e->cfg.chunk_layers > 0) layers = std::min<uint32_t>(layers, (uint32_t)e->cfg.chunk_layers);
+        pl.blocks_per_chunk = blocks;
+        pl.planes_per_chunk = 2 * std::max(layers, 1u);
+    }
+    return KV_OK;
+}
+
+// Sorts (slot, id) pairs by slot into the descriptor set: ids at dst[0..n), slots at dst[n..2n).
+void sorted_desc(kv_engine *e, const int32_t *ids, const int32_t *slots, int32_t n, int32_t *dst)
+{
+    e->sort_tmp.resize((size_t)n);
+    for (int32_t i = 0; i < n; i++) e->sort_tmp[(size_t)i] = {slots[i], ids[i]};
+    std::sort(e->sort_tmp.begin(), e->sort_tmp.end());
+    for (int32_t i = 0; i < n; i++) {
+        dst[i] = e->sort_tmp[(size_t)i].second;
+        dst[(size_t)n + i] = e->sort_tmp[(size_t)i].first;
+    }
+}
+
+// Copies of one chunk between staging and pool.  `to_host` picks the direction.
+int chunk_copies(kv_engine *e, bool to_host, uint8_t *stage, const int32_t *sorted_slots, uint32_t j0,
+                 uint32_t j1, uint32_t p0, uint32_t p1, hipStream_t s, int32_t &n_copies)
+{
+    const uint32_t nb = j1 - j0, np = p1 - p0;
+    uint64_t ss, ps;
+    pool_strides(e, ss, ps);
+    auto copy = [&](uint64_t pool_off, uint64_t stage_off, uint64_t bytes) -> hipError_t {
+        n_copies++;
+        return to_host ? hipMemcpyAsync(e->pool + pool_off, stage + stage_off, bytes, hipMemcpyDeviceToHost, s)
+                       : hipMemcpyAsync(stage + stage_off, e->pool + pool_off, bytes, hipMemcpyHostToDevice, s);
+    };
+    const bool block_first = e->cfg.host_layout == KV_HOST_BLOCK_FIRST;
+    uint32_t j = j0;
+    while (j < j1) {  // run of consecutive slots [j, r)
+        uint32_t r = j + 1;
+        while (r < j1 && sorted_slots[r] == sorted_slots[r - 1] + 1) r++;
+        const uint64_t slot = (uint64_t)sorted_slots[j];
+        if (block_first) {
+            if (np == e->n_planes) {  // whole blocks: the run is one range
+                HIPTRY(e, copy(slot * ss, (uint64_t)(j - j0) * np * e->seg, (uint64_t)(r - j) * np * e->seg));
+            } else {
+                for (uint32_t b = j; b < r; b++)
+                    HIPTRY(e, copy((uint64_t)sorted_slots[b] * ss + (uint64_t)p0 * ps,
+                                   (uint64_t)(b - j0) * np * e->seg, (uint64_t)np * e->seg));
+            }
+        } else {
+            for (uint32_t pl = p0; pl < p1; pl++)
+                HIPTRY(e, copy(slot * ss + (uint64_t)pl * ps,
+                               ((uint64_t)(pl - p0) * nb + (j - j0)) * e->seg, (uint64_t)(r - j) * e->seg));
+        }
+        j = r;
+    }
+    return KV_OK;
+}
+
+MoveParams stage_params(const kv_engine *e, uint8_t *stage, uint32_t nb, uint32_t p0, uint32_t np, int u)
+{
+    MoveParams p = base_params(e, u);
+    p.plane0 = p0;
+    p.n_planes = np;
+    p.far_out = p.far_in = stage;
+    uint64_t ss, ps;
+    if (e->cfg.host_layout == KV_HOST_BLOCK_FIRST) {
+        ss = (uint64_t)np * e->seg;
+        ps = e->seg;
+        p.plane_major = 0;
+    } else {
+        ss = e->seg;
+        ps = (uint64_t)nb * e->seg;
+        p.plane_major = 1;
+    }
+    // the kernel adds plane * ps with the absolute plane index: rebase to p0
+    p.far_out = p.far_in = stage - (uint64_t)p0 * ps;
+    p.far_slot_stride_out = p.far_slot_stride_in = ss;
+    p.far_plane_stride_out = p.far_plane_stride_in = ps;
+    return p;
+}
+
+int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+               const int32_t *is, int32_t ni)
+{
+    int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
+    int32_t *dd = e->desc_dev + (size_t)k * e->desc_cap;
+    int32_t *h_out = dh, *h_in = dh + 2 * (size_t)no;
+    int32_t *d_out = dd, *d_in = dd + 2 * (size_t)no;
+    constexpr int U = 4;
+    ChunkPlan po{}, pi{};
+    if (no > 0) {
+        int rc = plan_chunks(e, (uint32_t)no, po);
+        if (rc != KV_OK) return rc;
+        sorted_desc(e, oi, os, no, h_out);
+    }
+    if (ni > 0) {
+        int rc = plan_chunks(e, (uint32_t)ni, pi);
+        if (rc != KV_OK) return rc;
+        sorted_desc(e, ii, is, ni, h_in);
+    }
+    StageDir &so = e->st_out, &si = e->st_in;
+    if (no > 0) {
+        // pack kernels run on their own stream, after whatever stream_out already holds
+        HIPTRY(e, hipMemcpyAsync(d_out, h_out, 2 * (size_t)no * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
+        if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
+        HIPTRY(e, hipEventRecord(e->ev_join, e->s_out));
+        HIPTRY(e, hipStreamWaitEvent(so.kstream, e->ev_join, 0));
+    }
+    if (ni > 0) {
+        HIPTRY(e, hipMemcpyAsync(d_in, h_in, 2 * (size_t)ni * sizeof(int32_t), hipMemcpyHostToDevice, e->s_in));
+        if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
+    }
+    // chunk lists, enumerated in the same order for both directions and interleaved
+    struct Cur { uint32_t j0 = 0, p0 = 0; bool done = true; int c = 0; } co, ci;
+    co.done = no == 0;
+    ci.done = ni == 0;
+    int32_t n_ops = 0;
+    while (!co.done || !ci.done) {
+        if (!co.done) {
+            const uint32_t j1 = std::min<uint32_t>(co.j0 + po.blocks_per_chunk, (uint32_t)no);
+            const uint32_t p1 = std::min<uint32_t>(co.p0 + po.planes_per_chunk, e->n_planes);
+            const int b = co.c % kStageBufs;
+            if (so.used[b]) HIPTRY(e, hipStreamWaitEvent(so.kstream, so.copy_done[b], 0));
+            MoveParams p = stage_params(e, so.buf[b], j1 - co.j0, co.p0, p1 - co.p0, U);
+            p.out = DirDesc{d_out + co.j0, nullptr, j1 - co.j0, 0};
+            if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
+            const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.out.tiles);
+            launch_move<U>(e->vec, wgs, so.kstream, p);
+            HIPTRY(e, hipGetLastError());
+            HIPTRY(e, hipEventRecord(so.kernel_done[b], so.kstream));
+            HIPTRY(e, hipStreamWaitEvent(e->s_out, so.kernel_done[b], 0));
+            if (chunk_copies(e, true, so.buf[b], h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
+                return KV_EHIP;
+            HIPTRY(e, hipEventRecord(so.copy_done[b], e->s_out));
+            so.used[b] = true;
+            n_ops++;
+            co.c++;
+            co.p0 = p1;
+            if (co.p0 >= e->n_planes) { co.p0 = 0; co.j0 = j1; }
+            co.done = co.j0 >= (uint32_t)no;
+        }
+        if (!ci.done) {
+            const uint32_t j1 = std::min<uint32_t>(ci.j0 + pi.blocks_per_chunk, (uint32_t)ni);
+            const uint32_t p1 = std::min<uint32_t>(ci.p0 + pi.planes_per_chunk, e->n_planes);
+            const int b = ci.c % kStageBufs;
+            if (si.used[b]) HIPTRY(e, hipStreamWaitEvent(e->s_in, si.kernel_done[b], 0));
+            if (chunk_copies(e, false, si.buf[b], h_in + ni, ci.j0, j1, ci.p0, p1, e->s_in, n_ops) != KV_OK)
+                return KV_EHIP;
+            HIPTRY(e, hipEventRecord(si.copy_done[b], e->s_in));
+            HIPTRY(e, hipStreamWaitEvent(si.kstream, si.copy_done[b], 0));
+            MoveParams p = stage_params(e, si.buf[b], j1 - ci.j0, ci.p0, p1 - ci.p0, U);
+            p.in = DirDesc{d_in + ci.j0, nullptr, j1 - ci.j0, 0};
+            if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
+            const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.in.tiles);
+            launch_move<U>(e->vec, wgs, si.kstream, p);
+            HIPTRY(e, hipGetLastError());
+            HIPTRY(e, hipEventRecord(si.kernel_done[b], si.kstream));
+            si.used[b] = true;
+            n_ops++;
+            ci.c++;
+            ci.p0 = p1;
+            if (ci.p0 >= e->n_planes) { ci.p0 = 0; ci.j0 = j1; }
+            ci.done = ci.j0 >= (uint32_t)ni;
+        }
+    }
+    if (no > 0) HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
+    if (ni > 0) {
+        // stream_in has to see the last unpack kernels
+        for (int b = 0; b < kStageBufs; b++)
+            if (si.used[b]) HIPTRY(e, hipStreamWaitEvent(e->s_in, si.kernel_done[b], 0));
+        HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
+    }
+    HIPTRY(e, hipEventRecord(e->ring_out[k], e->s_out));
+    HIPTRY(e, hipEventRecord(e->ring_in[k], e->s_in));
+    e->acc.n_launches += n_ops;
+    return KV_OK;
+}
+
+int ensure_staging(kv_engine *e)
+{
+    if (e->st_out.buf[0]) return KV_OK;
+    uint64_t per_dir = e->cfg.staging_bytes ? e->cfg.staging_bytes : (128ull << 20);
+    uint64_t cap = per_dir / kStageBufs;
+    cap -= cap % 256;
+    if (cap < 2 * e->seg) return KV_EINVAL;
+    e->chunk_cap = cap;
+    for (StageDir *d : {&e->st_out, &e->st_in}) {
+        for (int b = 0; b < kStageBufs; b++) {
+            if (hipMalloc((void **)&d->buf[b], cap) != hipSuccess) {
+                (void)hipGetLastError();
+                return KV_ENOMEM;
+            }
+            HIPTRY(e, hipEventCreateWithFlags(&d->kernel_done[b], hipEventDisableTiming));
+            HIPTRY(e, hipEventCreateWithFlags(&d->copy_done[b], hipEventDisableTiming));
+        }
+        HIPTRY(e, hipStreamCreateWithFlags(&d->kstream, hipStreamNonBlocking));
+    }
+    return KV_OK;
+}
+
+int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+             const int32_t *is, int32_t ni)
+{
+    if (!e) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    int rc = admit(&e->cfg, e->marks, oi, os, no, ii, is, ni);
+    if (rc != KV_OK) return rc;
+    if (no == 0 && ni == 0) return KV_OK;
+    int path = e->cfg.path;
+    if (path == KV_PATH_AUTO) path = (no > 0 && ni > 0) ? KV_PATH_FUSED : KV_PATH_ZEROCOPY;
+    if (path == KV_PATH_SDMA_STAGED) {
+        rc = ensure_staging(e);
+        if (rc != KV_OK) return rc;
+    }
+    open_batch(e);
+    if (path == KV_PATH_NAIVE) {
+        rc = run_naive(e, oi, os, no, ii, is, ni);
+    } else {
+        int k;
+        rc = acquire_ring(e, k);
+        if (rc != KV_OK) return rc;
+        int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
+        if (path != KV_PATH_SDMA_STAGED) {
+            if (no) {
+                memcpy(dh, oi, (size_t)no * sizeof(int32_t));
+                memcpy(dh + no, os, (size_t)no * sizeof(int32_t));
+            }
+            if (ni) {
+                memcpy(dh + 2 * (size_t)no, ii, (size_t)ni * sizeof(int32_t));
+                memcpy(dh + 2 * (size_t)no + ni, is, (size_t)ni * sizeof(int32_t));
+            }
+            rc = run_zero_copy(e, path, k, no, ni);
+        } else {
+            rc = run_staged(e, k, oi, os, no, ii, is, ni);
+        }
+    }
+    if (rc != KV_OK) return rc;
+    e->acc.bytes_out += (uint64_t)no * e->block_bytes;
+    e->acc.bytes_in += (uint64_t)ni * e->block_bytes;
+    e->acc.path_used = path;
+    return KV_OK;
+}
+
+void free_engine(kv_engine *e)
+{
+    if (!e) return;
+    auto ev = [](hipEvent_t &x) { if (x) { (void)hipEventDestroy(x); x = nullptr; } };
+    for (int k = 0; k < kRing; k++) { ev(e->ring_out[k]); ev(e->ring_in[k]); }
+    ev(e->ev_o0); ev(e->ev_o1); ev(e->ev_i0); ev(e->ev_i1); ev(e->ev_join); ev(e->ev_join2);
+    for (StageDir *d : {&e->st_out, &e->st_in}) {
+        for (int b = 0; b < kStageBufs; b++) {
+            if (d->buf[b]) (void)hipFree(d->buf[b]);
+            ev(d->kernel_done[b]);
+            ev(d->copy_done[b]);
+        }
+        if (d->kstream) (void)hipStreamDestroy(d->kstream);
+    }
+    if (e->desc_host) (void)hipHostFree(e->desc_host);
+    if (e->desc_dev) (void)hipFree(e->desc_dev);
+    if (e->own_pool && e->pool) (void)hipHostFree(e->pool);
+    if (e->own_streams) {
+        if (e->s_out) (void)hipStreamDestroy(e->s_out);
+        if (e->s_in) (void)hipStreamDestroy(e->s_in);
+    }
+    delete e;
+}
+
+double median(std::vector<double> v)
+{
+    std::sort(v.begin(), v.end());
+    return v[v.size() / 2];
+}
+
+}  // namespace
+
+extern "C" {
+
+uint64_t kv_seg_bytes(const kv_config *c) { return config_ok(c) ? seg_of(c) : 0; }
+uint64_t kv_block_bytes(const kv_config *c) { return config_ok(c) ? 2ull * c->n_layers * seg_of(c) : 0; }
+uint64_t kv_cache_bytes(const kv_config *c)
+{
+    return config_ok(c) ? kv_block_bytes(c) * (uint64_t)c->n_hbm_blocks : 0;
+}
+uint64_t kv_pool_bytes(const kv_config *c)
+{
+    return config_ok(c) ? kv_block_bytes(c) * (uint64_t)c->n_host_slots : 0;
+}
+
+int kv_validate(const kv_config *cfg, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+                const int32_t *is, int32_t ni)
+{
+    if (!config_ok(cfg)) return KV_EINVAL;
+    Marks mk;
+    mk.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
+    return admit(cfg, mk, oi, os, no, ii, is, ni);
+}
+
+int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host_pool, void *stream_out,
+              void *stream_in)
+{
+    if (!out) return KV_EINVAL;
+    *out = nullptr;
+    if (!config_ok(cfg) || !hbm_cache) return KV_EINVAL;
+    if ((stream_out == nullptr) != (stream_in == nullptr)) return KV_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0) {
+        (void)hipGetLastError();
+        fprintf(stderr, "duplexkv: no HIP device is visible\n");
+        return KV_EHIP;
+    }
+    kv_engine *e = new (std::nothrow) kv_engine;
+    if (!e) return KV_ENOMEM;
+    e->cfg = *cfg;
+    e->seg = seg_of(cfg);
+    e->n_planes = 2u * (uint32_t)cfg->n_layers;
+    e->block_bytes = kv_block_bytes(cfg);
+    e->cache_bytes = kv_cache_bytes(cfg);
+    e->pool_bytes = kv_pool_bytes(cfg);
+    e->hbm = (uint8_t *)hbm_cache;
+    int rc = KV_OK;
+    auto fail = [&](int code) { free_engine(e); return code; };
+
+    if (hipGetDevice(&e->device) != hipSuccess) return fail(KV_EHIP);
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, e->device) != hipSuccess) return fail(KV_EHIP);
+    e->n_cus = prop.multiProcessorCount;
+
+    // the cache pointer must be a device allocation that really spans cache_bytes
+    {
+        hipDeviceptr_t base = nullptr;
+        size_t span = 0;
+        if (hipMemGetAddressRange(&base, &span, (hipDeviceptr_t)hbm_cache) != hipSuccess) {
+            (void)hipGetLastError();
+            fprintf(stderr, "duplexkv: hbm_cache is not a device allocation\n");
+            return fail(KV_EINVAL);
+        }
+        const uintptr_t lo = (uintptr_t)base, hi = lo + span, p = (uintptr_t)hbm_cache;
+        if (p < lo || p + e->cache_bytes > hi) {
+            fprintf(stderr, "duplexkv: hbm_cache allocation is smaller than the configured cache\n");
+            return fail(KV_EINVAL);
+        }
+    }
+    if (host_pool) {
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, host_pool) != hipSuccess || at.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            fprintf(stderr, "duplexkv: host_pool is not pinned host memory\n");
+            return fail(KV_EINVAL);
+        }
+        hipDeviceptr_t base = nullptr;
+        size_t span = 0;
+        if (hipMemGetAddressRange(&base, &span, (hipDeviceptr_t)host_pool) == hipSuccess) {
+            const uintptr_t lo = (uintptr_t)base, hi = lo + span, p = (uintptr_t)host_pool;
+            if (p < lo || p + e->pool_bytes > hi) {
+                fprintf(stderr, "duplexkv: host_pool allocation is smaller than the configured pool\n");
+                return fail(KV_EINVAL);
+            }
+        } else {
+            (void)hipGetLastError();
+        }
+        e->pool = (uint8_t *)host_pool;
+    } else {
+        if (hipHostMalloc((void **)&e->pool, e->pool_bytes, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            e->pool = nullptr;
+            return fail(KV_ENOMEM);
+        }
+        e->own_pool = true;
+    }
+    e->vec = pick_vec(e);
+
+    if (stream_out) {
+        e->s_out = (hipStream_t)stream_out;
+        e->s_in = (hipStream_t)stream_in;
+    } else {
+        e->own_streams = true;
+        if (hipStreamCreateWithFlags(&e->s_out, hipStreamNonBlocking) != hipSuccess ||
+            hipStreamCreateWithFlags(&e->s_in, hipStreamNonBlocking) != hipSuccess)
+            return fail(KV_EHIP);
+    }
+    // one call names at most min(blocks, slots) ids over both directions
+    e->desc_cap = 2 * (size_t)std::min(cfg->n_hbm_blocks, cfg->n_host_slots) + 16;
+    if (hipHostMalloc((void **)&e->desc_host, kRing * e->desc_cap * sizeof(int32_t), hipHostMallocDefault) !=
+            hipSuccess ||
+        hipMalloc((void **)&e->desc_dev, kRing * e->desc_cap * sizeof(int32_t)) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(KV_ENOMEM);
+    }
+    bool ok = true;
+    for (int k = 0; k < kRing; k++) {
+        ok = ok && hipEventCreateWithFlags(&e->ring_out[k], hipEventDisableTiming) == hipSuccess;
+        ok = ok && hipEventCreateWithFlags(&e->ring_in[k], hipEventDisableTiming) == hipSuccess;
+    }
+    for (hipEvent_t *x : {&e->ev_o0, &e->ev_o1, &e->ev_i0, &e->ev_i1}) ok = ok && hipEventCreate(x) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&e->ev_join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&e->ev_join2, hipEventDisableTiming) == hipSuccess;
+    if (!ok) return fail(KV_EHIP);
+    e->marks.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
+    if (cfg->path == KV_PATH_SDMA_STAGED) {
+        rc = ensure_staging(e);
+        if (rc != KV_OK) return fail(rc);
+    }
+    *out = e;
+    return KV_OK;
+}
+
+int kv_destroy(kv_engine *e)
+{
+    if (!e) return KV_EINVAL;
+    (void)hipStreamSynchronize(e->s_out);
+    (void)hipStreamSynchronize(e->s_in);
+    if (e->st_out.kstream) (void)hipStreamSynchronize(e->st_out.kstream);
+    if (e->st_in.kstream) (void)hipStreamSynchronize(e->st_in.kstream);
+    free_engine(e);
+    return KV_OK;
+}
+
+int kv_swap_out(kv_engine *e, const int32_t *ids, const int32_t *slots, int32_t n)
+{
+    return transfer(e, ids, slots, n, nullptr, nullptr, 0);
+}
+
+int kv_swap_in(kv_engine *e, const int32_t *slots, const int32_t *ids, int32_t n)
+{
+    return transfer(e, nullptr, nullptr, 0, ids, slots, n);
+}
+
+int kv_rotate(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+              const int32_t *is, int32_t ni)
+{
+    return transfer(e, oi, os, no, ii, is, ni);
+}
+
+int kv_wait(kv_engine *e)
+{
+    if (!e) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    HIPTRY(e, hipStreamSynchronize(e->s_out));
+    HIPTRY(e, hipStreamSynchronize(e->s_in));
+    if (e->st_in.kstream) HIPTRY(e, hipStreamSynchronize(e->st_in.kstream));
+    if (e->st_out.kstream) HIPTRY(e, hipStreamSynchronize(e->st_out.kstream));
+    for (int k = 0; k < kRing; k++) e->ring_used[k] = false;
+    for (StageDir *d : {&e->st_out, &e->st_in})
+        for (int b = 0; b < kStageBufs; b++) d->used[b] = false;
+    if (e->batch_open) {
+        e->acc.ms_e2e = now_ms() - e->t0;
+        float ms = 0;
+        if (e->have_o) {
+            HIPTRY(e, hipEventElapsedTime(&ms, e->ev_o0, e->ev_o1));
+            e->acc.ms_out = ms;
+        }
+        if (e->have_i) {
+            HIPTRY(e, hipEventElapsedTime(&ms, e->ev_i0, e->ev_i1));
+            e->acc.ms_in = ms;
+        }
+        e->last = e->acc;
+        e->batch_open = false;
+    }
+    return KV_OK;
+}
+
+int kv_host_pool(kv_engine *e, void **ptr, uint64_t *bytes)
+{
+    if (!e || !ptr || !bytes) return KV_EINVAL;
+    *ptr = e->pool;
+    *bytes = e->pool_bytes;
+    return KV_OK;
+}
+
+int kv_last_stats(kv_engine *e, kv_stats *out)
+{
+    if (!e || !out) return KV_EINVAL;
+    *out = e->last;
+    return KV_OK;
+}
+
+int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double *d2h_duplex,
+                  double *h2d_duplex)
+{
+    if (bytes == 0 || reps <= 0 || !d2h || !h2d || !d2h_duplex || !h2d_duplex) return KV_EINVAL;
+    kv_engine *e = nullptr;  // HIPTRY wants one; no engine state here
+    void *ha = nullptr, *hb = nullptr, *da = nullptr, *db = nullptr;
+    hipStream_t s1 = nullptr, s2 = nullptr;
+    int rc = KV_OK;
+    auto cleanup = [&]() {
+        if (ha) (void)hipHostFree(ha);
+        if (hb) (void)hipHostFree(hb);
+        if (da) (void)hipFree(da);
+        if (db) (void)hipFree(db);
+        if (s1) (void)hipStreamDestroy(s1);
+        if (s2) (void)hipStreamDestroy(s2);
+    };
+    if (hipHostMalloc(&ha, bytes, hipHostMallocDefault) != hipSuccess ||
+        hipHostMalloc(&hb, bytes, hipHostMallocDefault) != hipSuccess ||
+        hipMalloc(&da, bytes) != hipSuccess || hipMalloc(&db, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        cleanup();
+        return KV_ENOMEM;
+    }
+    memset(ha, 1, bytes);
+    memset(hb, 2, bytes);
+    auto body = [&]() -> int {
+        HIPTRY(e, hipMemset(da, 3, bytes));
+        HIPTRY(e, hipMemset(db, 4, bytes));
+        HIPTRY(e, hipStreamCreateWithFlags(&s1, hipStreamNonBlocking));
+        HIPTRY(e, hipStreamCreateWithFlags(&s2, hipStreamNonBlocking));
+        std::vector<double> t[4];
+        for (int mode = 0; mode < 3; mode++) {
+            for (int it = 0; it < reps + 2; it++) {
+                HIPTRY(e, hipDeviceSynchronize());
+                const double a = now_ms();
+                if (mode != 1) HIPTRY(e, hipMemcpyAsync(ha, da, bytes, hipMemcpyDeviceToHost, s1));
+                if (mode != 0) HIPTRY(e, hipMemcpyAsync(db, hb, bytes, hipMemcpyHostToDevice, s2));
+                double t_out = 0, t_in = 0;
+                if (mode != 1) { HIPTRY(e, hipStreamSynchronize(s1)); t_out = now_ms() - a; }
+                if (mode != 0) { HIPTRY(e, hipStreamSynchronize(s2)); t_in = now_ms() - a; }
+                if (it < 2) continue;
+                if (mode == 0) t[0].push_back(t_out);
+                if (mode == 1) t[1].push_back(t_in);
+                if (mode == 2) {  // both directions are charged the wall time of the pair
+                    const double w = std::max(t_out, t_in);
+                    t[2].push_back(w);
+                    t[3].push_back(w);
+                }
+            }
+        }
+        *d2h = bytes / median(t[0]) / 1e6;
+        *h2d = bytes / median(t[1]) / 1e6;
+        *d2h_duplex = bytes / median(t[2]) / 1e6;
+        *h2d_duplex = bytes / median(t[3]) / 1e6;
+        return KV_OK;
+    };
+    rc = body();
+    (void)hipDeviceSynchronize();
+    cleanup();
+    return rc;
+}
+
+const char *kv_strerror(int code)
+{
+    switch (code) {
+    case KV_OK: return "ok";
+    case KV_EINVAL: return "invalid argument or configuration";
+    case KV_ERANGE: return "block id or host slot out of range";
+    case KV_EDUP: return "duplicate id within one list";
+    case KV_EOVERLAP: return "block or slot named for both directions";
+    case KV_ENOMEM: return "allocation failed";
+    case KV_EHIP: return "HIP runtime failure";
+    case KV_EUNSUP: return "path cannot serve this shape or request";
+    default: return "unknown code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,191 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI, bit for bit."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_oracle as O
+from paper_2601_20309_amd import binding as B
+from paper_2601_20309_amd import workloads as W
+from tests.gpu_harness import GpuCase, make_case
+from tests import kvviews as V
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [B.KV_HOST_BLOCK_FIRST, B.KV_HOST_LAYER_FIRST]
+PATHS = [B.KV_PATH_AUTO, B.KV_PATH_FUSED, B.KV_PATH_ZEROCOPY, B.KV_PATH_SDMA_STAGED, B.KV_PATH_NAIVE]
+
+
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name", ["tiny", "ragged", "small8b"])
+def test_rotate_matches_oracle(name, layout, path):
+    case, rot = make_case(name, layout, path)
+    case.rotate(rot)
+    case.check()
+    st = case.eng.kv_last_stats()
+    blk = B.kv_block_bytes(case.cfg)
+    assert st["bytes_out"] == len(rot.out_ids) * blk and st["bytes_in"] == len(rot.in_ids) * blk
+    # and back again: the inverse rotation restores the named blocks
+    case.rotate(rot.inverse())
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_SDMA_STAGED, B.KV_PATH_NAIVE])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_single_directions_and_round_trip(layout, path):
+    case, rot = make_case("small8b", layout, path)
+    case.swap_out(rot.out_ids, rot.out_slots)
+    case.check()
+    case.swap_in(rot.in_slots, rot.in_ids)
+    case.check()
+    # the swapped-out copies come back: first into their own blocks (identity) ...
+    case.swap_in(rot.out_slots, rot.out_ids)
+    case.check()
+    # ... then into other blocks (a block permutation)
+    n = min(len(rot.out_slots), len(rot.in_ids))
+    case.swap_in(rot.out_slots[:n], rot.in_ids[:n][::-1].copy())
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_unbalanced_empty_and_one_block(path):
+    sh = W.SHAPES["small8b"]
+    for n_out, n_in in [(40, 3), (3, 40), (1, 1), (0, 5), (5, 0), (0, 0)]:
+        rot = W.simple_rotation(sh, n_out, n_in, seed=n_out * 100 + n_in)
+        case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, path, rot=rot)
+        case.rotate(rot)
+        case.check()
+        case.close()
+
+
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY, B.KV_PATH_SDMA_STAGED])
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_maximum_lists(layout, path):
+    """Every host slot in use: half filled from HBM, half emptied into it."""
+    sh = W.SHAPES["tiny"]
+    half = sh.n_host_slots // 2
+    rot = W.simple_rotation(sh, half, half, seed=3, n_used=sh.n_hbm_blocks // 2)
+    case, _ = make_case(sh, layout, path, rot=rot)
+    case.rotate(rot)
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_rejections_enqueue_nothing(layout):
+    case, rot = make_case("tiny", layout, B.KV_PATH_AUTO)
+    nb, ns = case.shape.n_hbm_blocks, case.shape.n_host_slots
+    bad = [
+        (W.Rotation(np.array([nb]), np.array([0]), np.array([], int), np.array([], int)), B.KV_ERANGE),
+        (W.Rotation(np.array([0]), np.array([-1]), np.array([], int), np.array([], int)), B.KV_ERANGE),
+        (W.Rotation(np.array([3, 3]), np.array([0, 1]), np.array([], int), np.array([], int)), B.KV_EDUP),
+        (W.Rotation(np.array([], int), np.array([], int), np.array([7, 8]), np.array([2, 2])), B.KV_EDUP),
+        (W.Rotation(np.array([5]), np.array([0]), np.array([5]), np.array([1])), B.KV_EOVERLAP),
+        (W.Rotation(np.array([5]), np.array([4]), np.array([6]), np.array([4])), B.KV_EOVERLAP),
+        (W.Rotation(np.array([5, 6]), np.array([0, 0]), np.array([5]), np.array([1])), B.KV_EDUP),
+    ]
+    for r, code in bad:
+        case.rotate(r, expect=code)
+    case.check()               # nothing moved
+    case.rotate(rot)           # and the engine still works afterwards
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY, B.KV_PATH_SDMA_STAGED])
+def test_many_calls_without_wait_wrap_the_descriptor_ring(path):
+    sh = W.SHAPES["small8b"]
+    rng = np.random.default_rng(8)
+    perm = rng.permutation(sh.n_hbm_blocks).astype(np.int32)
+    sperm = rng.permutation(sh.n_host_slots).astype(np.int32)
+    rot0 = W.Rotation(perm[:0], sperm[:0], perm[:0], sperm[:0])
+    case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, path, rot=rot0)
+    # 20 disjoint small rotations back to back, more than the ring holds
+    for c in range(20):
+        o = perm[c * 6:c * 6 + 3]; i = perm[c * 6 + 3:c * 6 + 6]
+        so = sperm[c * 6:c * 6 + 3]; si = sperm[c * 6 + 3:c * 6 + 6]
+        case.rotate(W.Rotation(o, so, i, si))
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY, B.KV_PATH_SDMA_STAGED])
+def test_caller_owned_pool_and_streams(path):
+    case, rot = make_case("small8b", B.KV_HOST_LAYER_FIRST, path, own_pool=False, own_streams=False)
+    case.rotate(rot)
+    # work enqueued on the caller's in-stream afterwards sees the swapped-in blocks
+    with torch.cuda.stream(case.streams[1]):
+        snap = case.dev_cache.clone()
+    case.check()
+    assert torch.equal(snap.cpu(), case.dev_cache.cpu())
+    case.close()
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("chunk_layers,staging", [(0, 2 << 20), (1, 2 << 20), (2, 8 << 20), (0, 1 << 20)])
+def test_staged_chunking_small_buffers(layout, chunk_layers, staging):
+    """Staging far smaller than the rotation: many chunks, both buffers reused,
+    plane ranges and block ranges split."""
+    case, rot = make_case("small8b", layout, B.KV_PATH_SDMA_STAGED, chunk_layers=chunk_layers,
+                          staging_bytes=staging)
+    case.rotate(rot)
+    case.check()
+    assert case.eng.kv_last_stats()["n_launches"] > 4
+    case.rotate(rot.inverse())
+    case.check()
+    case.close()
+
+
+def test_staged_contiguous_slots_merge_into_few_copies():
+    sh = W.SHAPES["small8b"]
+    rot = W.simple_rotation(sh, 32, 32, seed=4, contiguous_slots=True)
+    case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_SDMA_STAGED, rot=rot)
+    case.rotate(rot)
+    case.check()
+    # 32 blocks x 256 KiB = 8 MiB per direction fits one chunk: 1 kernel + 1 copy each way
+    assert case.eng.kv_last_stats()["n_launches"] == 4
+    case.close()
+
+
+@pytest.mark.parametrize("max_wgs", [1, 7, 64])
+def test_workgroup_cap(max_wgs):
+    case, rot = make_case("small8b", B.KV_HOST_BLOCK_FIRST, B.KV_PATH_AUTO, max_copy_wgs=max_wgs)
+    case.rotate(rot)
+    case.check()
+    case.close()
+
+
+def test_unaligned_segments_use_narrow_vectors():
+    """Segment sizes that are not multiples of 16 bytes (2-byte and 1-byte lanes)."""
+    for sh in [W.KVShape(2, 1, 3, 1, n_hbm_blocks=11, n_host_slots=9, elem_bytes=2),   # 6 B
+               W.KVShape(2, 1, 7, 3, n_hbm_blocks=11, n_host_slots=9, elem_bytes=1),   # 21 B
+               W.KVShape(2, 3, 5, 4, n_hbm_blocks=11, n_host_slots=9, elem_bytes=2)]:  # 120 B
+        rot = W.simple_rotation(sh, 4, 3, seed=2)
+        oshape = O.shape_of(sh, 0)
+        rng = np.random.default_rng(3)
+        cache = rng.integers(0, 256, O.cache_bytes(oshape), dtype=np.uint8)
+        pool = rng.integers(0, 256, O.pool_bytes(oshape), dtype=np.uint8)
+        if cache.size % 2:
+            continue
+        for path in (B.KV_PATH_AUTO, B.KV_PATH_SDMA_STAGED):
+            case = GpuCase(sh, 0, path, cache.view(np.uint16), pool.view(np.uint16))
+            case.rotate(rot)
+            case.check()
+            case.close()
+
+
+def test_create_rejects_undersized_cache():
+    sh = W.SHAPES["tiny"]
+    cfg = B.make_config(sh)
+    # a separate small allocation, not a slice of a larger one
+    small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    big_cfg = B.make_config(dataclasses.replace(sh, n_hbm_blocks=1 << 20))
+    with pytest.raises(B.KVError) as ei:
+        B.Engine(big_cfg, small.data_ptr())
+    assert ei.value.code == B.KV_EINVAL
+    with pytest.raises(B.KVError):
+        B.Engine(cfg, small.data_ptr(), host_pool_ptr=small.data_ptr())   # pool must be host memory
