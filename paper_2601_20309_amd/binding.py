@@ -30,7 +30,7 @@ EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", 
 class kv_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes", "n_hbm_blocks",
-        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "reserved")] + \
+        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "vecs_per_lane")] + \
         [("staging_bytes", C.c_uint64)]
 
 
@@ -85,11 +85,11 @@ lib = _load()
 
 
 def make_config(shape, host_layout=KV_HOST_BLOCK_FIRST, path=KV_PATH_AUTO, chunk_layers=0,
-                max_copy_wgs=0, staging_bytes=0) -> kv_config:
+                max_copy_wgs=0, staging_bytes=0, vecs_per_lane=0) -> kv_config:
     """kv_config from any object carrying the KV shape attributes."""
     return kv_config(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
                      shape.elem_bytes, shape.n_hbm_blocks, shape.n_host_slots, host_layout, path,
-                     chunk_layers, max_copy_wgs, 0, staging_bytes)
+                     chunk_layers, max_copy_wgs, vecs_per_lane, staging_bytes)
 
 
 def _ids(a):
@@ -158,6 +158,18 @@ class Engine:
         pi, ni, k3 = _ids(in_block_ids); pis, ni2, k4 = _ids(in_host_slots)
         assert no == no2 and ni == ni2
         return lib.kv_rotate(self._h, po, ps, no, pi, pis, ni)
+
+    def prepare(self, out_block_ids, out_host_slots, in_block_ids, in_host_slots):
+        """Marshal one rotation's id lists once; returns a zero-argument callable
+        that performs the kv_rotate call (for loops that repeat a rotation)."""
+        po, no, k1 = _ids(out_block_ids); ps, no2, k2 = _ids(out_host_slots)
+        pi, ni, k3 = _ids(in_block_ids); pis, ni2, k4 = _ids(in_host_slots)
+        assert no == no2 and ni == ni2
+        h, f = self._h, lib.kv_rotate
+
+        def call(_keep=(k1, k2, k3, k4)):
+            return f(h, po, ps, no, pi, pis, ni)
+        return call
 
     def kv_wait(self) -> int:
         return lib.kv_wait(self._h)

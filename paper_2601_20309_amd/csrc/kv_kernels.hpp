@@ -48,10 +48,20 @@ struct MoveParams {
     DirDesc out, in;
 };
 
-template <typename V>
-__device__ __forceinline__ V ld_stream(const V *p) { return __builtin_nontemporal_load(p); }
-template <typename V>
-__device__ __forceinline__ void st_stream(V *p, V v) { __builtin_nontemporal_store(v, p); }
+// HBM-side accesses: every byte is touched once, so NT = true marks them
+// non-temporal (no reuse worth keeping in L2 / MALL).
+template <bool NT, typename V>
+__device__ __forceinline__ V ld_hbm(const V *p)
+{
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT, typename V>
+__device__ __forceinline__ void st_hbm(V *p, V v)
+{
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
 
 // Tile t of direction d -> byte offsets of its segment and first vector index.
 __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d, uint32_t t,
@@ -84,7 +94,7 @@ __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d, ui
 // Workgroup g takes tiles g, g + G, ... of BOTH directions; a direction that
 // has run out of tiles is simply skipped, so the lists may differ in length or
 // be empty.
-template <typename V, int U>
+template <typename V, int U, bool NT>
 __global__ __launch_bounds__(kThreads) void kv_move_kernel(const MoveParams p)
 {
     const uint32_t tid = threadIdx.x;
@@ -121,7 +131,7 @@ __global__ __launch_bounds__(kThreads) void kv_move_kernel(const MoveParams p)
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 const uint32_t v = v0_o + u * kThreads + tid;
-                if (v < p.vec_per_seg) vo[u] = ld_stream(src_o + v);
+                if (v < p.vec_per_seg) vo[u] = ld_hbm<NT>(src_o + v);
             }
 #pragma unroll
             for (int u = 0; u < U; u++) {
@@ -133,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void kv_move_kernel(const MoveParams p)
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 const uint32_t v = v0_i + u * kThreads + tid;
-                if (v < p.vec_per_seg) st_stream(dst_i + v, vi[u]);
+                if (v < p.vec_per_seg) st_hbm<NT>(dst_i + v, vi[u]);
             }
         }
     }
