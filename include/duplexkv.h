@@ -168,6 +168,25 @@ int kv_last_stats(kv_engine *engine, kv_stats *out);
 int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d,
                   double *d2h_duplex, double *h2d_duplex);
 
+/*
+ * Synthetic decode reader: the stand-in for the model execution that runs
+ * while blocks rotate (Section 4.3.2, "Cross-iteration pipeline to overlap
+ * execution with rotation").  Streams every segment of the named HBM blocks,
+ * layer by layer, `passes` times (1..256), on a stream of the engine's own so
+ * that it overlaps kv_rotate, and reduces what it read to the sum modulo 2^64
+ * of all little-endian 32-bit words (a block named twice counts twice).  Read
+ * only.  Needs segments that are multiples of 16 bytes (KV_EUNSUP otherwise).
+ * max_wgs caps its workgroups (0 = engine picks).  One reader at a time:
+ * kv_reader_wait() must come before the next kv_reader_start().
+ */
+int kv_reader_start(kv_engine *engine, const int32_t *block_ids, int32_t n, int32_t passes, int32_t max_wgs);
+
+/*
+ * Waits for the reader.  checksum: the sum over all passes.  ms_per_pass: NULL
+ * or an array of `passes` doubles, device time of each pass (HIP events).
+ */
+int kv_reader_wait(kv_engine *engine, uint64_t *checksum, double *ms_per_pass);
+
 const char *kv_strerror(int code);
 
 #ifdef __cplusplus

@@ -219,6 +219,39 @@ int okv_swap_in(const okv_shape *s, uint8_t *hbm, uint8_t *pool,
 }
 
 /*
+ * Synthetic decode reader (stands in for the model execution that runs while
+ * blocks rotate, Section 4.3.2 "Cross-iteration pipeline"): what a pass over
+ * the KV of the running requests reads.  The result is the sum, modulo 2^64,
+ * of every little-endian 32-bit word of every segment (all layers, K and V)
+ * of the named blocks; a block named twice counts twice.  Segment size must
+ * be a multiple of 4 bytes.
+ */
+int okv_read_checksum(const okv_shape *s, const uint8_t *hbm, const int32_t *ids, int32_t n,
+                      uint64_t *sum_out)
+{
+    if (!shape_ok(s) || list_bad(ids, n) || !sum_out || (n > 0 && !hbm))
+        return OKV_EINVAL;
+    if (okv_seg_bytes(s) % 4u != 0)
+        return OKV_EINVAL;
+    if (any_out_of_range(ids, n, s->n_hbm_blocks))
+        return OKV_ERANGE;
+    uint64_t sum = 0;
+    uint64_t words = okv_seg_bytes(s) / 4u;
+    for (int32_t l = 0; l < s->n_layers; l++)
+        for (int32_t kv = 0; kv < 2; kv++)
+            for (int32_t i = 0; i < n; i++) {
+                const uint8_t *p = hbm + okv_hbm_offset(s, l, kv, ids[i]);
+                for (uint64_t w = 0; w < words; w++) {
+                    uint32_t v = (uint32_t)p[4 * w] | ((uint32_t)p[4 * w + 1] << 8) |
+                                 ((uint32_t)p[4 * w + 2] << 16) | ((uint32_t)p[4 * w + 3] << 24);
+                    sum += v;
+                }
+            }
+    *sum_out = sum;
+    return OKV_OK;
+}
+
+/*
  * The same rotation with the two block lists dealt out over host threads in
  * contiguous shares (thread t takes blocks [t*n/T, (t+1)*n/T) of each list).
  * Only the CPU-baseline timing uses this; the copies are the same calls.

@@ -64,6 +64,8 @@ def lib() -> C.CDLL:
         L.okv_swap_out.argtypes = [ps, C.c_void_p, C.c_void_p, p32, p32, C.c_int32]
         L.okv_swap_in.restype = C.c_int
         L.okv_swap_in.argtypes = [ps, C.c_void_p, C.c_void_p, p32, p32, C.c_int32]
+        L.okv_read_checksum.restype = C.c_int
+        L.okv_read_checksum.argtypes = [ps, C.c_void_p, p32, C.c_int32, C.POINTER(C.c_uint64)]
         _lib = L
     return _lib
 
@@ -139,3 +141,11 @@ def swap_in(s, hbm, pool, slots, ids) -> int:
     psl, n, k1 = _ids(slots); pi, n2, k2 = _ids(ids)
     assert n == n2
     return lib().okv_swap_in(C.byref(s), _buf(hbm), _buf(pool), psl, pi, n)
+
+
+def read_checksum(s, hbm, ids):
+    """(code, sum of all 32-bit words of the named blocks modulo 2**64)."""
+    pi, n, k1 = _ids(ids)
+    out = C.c_uint64(0)
+    rc = lib().okv_read_checksum(C.byref(s), _buf(hbm), pi, n, C.byref(out))
+    return rc, int(out.value)

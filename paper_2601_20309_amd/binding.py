@@ -24,7 +24,8 @@ PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"
 
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
            "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
-           "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_strerror"]
+           "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
+           "kv_strerror"]
 
 
 class kv_config(C.Structure):
@@ -76,6 +77,10 @@ def _load() -> C.CDLL:
     L.kv_last_stats.argtypes = [C.c_void_p, C.POINTER(kv_stats)]
     L.kv_probe_link.restype = C.c_int
     L.kv_probe_link.argtypes = [C.c_uint64, C.c_int32] + [C.POINTER(C.c_double)] * 4
+    L.kv_reader_start.restype = C.c_int
+    L.kv_reader_start.argtypes = [C.c_void_p, p32, C.c_int32, C.c_int32, C.c_int32]
+    L.kv_reader_wait.restype = C.c_int
+    L.kv_reader_wait.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
     L.kv_strerror.restype = C.c_char_p
     L.kv_strerror.argtypes = [C.c_int]
     return L
@@ -193,6 +198,19 @@ class Engine:
         if rc != KV_OK:
             raise KVError(rc, "kv_last_stats")
         return {f: getattr(st, f) for f, _ in kv_stats._fields_}
+
+    def kv_reader_start(self, block_ids, passes: int = 1, max_wgs: int = 0) -> int:
+        pi, n, k1 = _ids(block_ids)
+        self._reader_passes = passes
+        return lib.kv_reader_start(self._h, pi, n, passes, max_wgs)
+
+    def kv_reader_wait(self):
+        """(code, checksum over all passes, [ms of each pass])."""
+        n = getattr(self, "_reader_passes", 0)
+        ms = (C.c_double * max(n, 1))()
+        cs = C.c_uint64(0)
+        rc = lib.kv_reader_wait(self._h, C.byref(cs), ms)
+        return rc, int(cs.value), [ms[i] for i in range(n)]
 
     def kv_destroy(self) -> int:
         if self._h:

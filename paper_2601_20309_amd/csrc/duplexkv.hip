@@ -163,6 +163,15 @@ struct kv_engine {
     // staging for SDMA_STAGED
     StageDir st_out, st_in;
     uint64_t chunk_cap = 0;
+
+    // synthetic decode reader
+    hipStream_t s_read = nullptr;
+    int32_t *read_ids = nullptr;               // device, n_hbm_blocks ints
+    int32_t *read_ids_host = nullptr;          // pinned
+    unsigned long long *read_acc = nullptr;    // device
+    unsigned long long *read_acc_host = nullptr;  // pinned
+    std::vector<hipEvent_t> read_ev;           // passes + 1 timestamps
+    int32_t read_passes = 0;
 };
 
 namespace {
@@ -727,6 +736,12 @@ void free_engine(kv_engine *e)
         }
         if (d->kstream) (void)hipStreamDestroy(d->kstream);
     }
+    if (e->s_read) (void)hipStreamDestroy(e->s_read);
+    if (e->read_ids) (void)hipFree(e->read_ids);
+    if (e->read_ids_host) (void)hipHostFree(e->read_ids_host);
+    if (e->read_acc) (void)hipFree(e->read_acc);
+    if (e->read_acc_host) (void)hipHostFree(e->read_acc_host);
+    for (hipEvent_t &x : e->read_ev) ev(x);
     if (e->desc_host) (void)hipHostFree(e->desc_host);
     if (e->desc_dev) (void)hipFree(e->desc_dev);
     if (e->own_pool && e->pool) (void)hipHostFree(e->pool);
@@ -879,6 +894,7 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
 int kv_destroy(kv_engine *e)
 {
     if (!e) return KV_EINVAL;
+    if (e->s_read) (void)hipStreamSynchronize(e->s_read);
     (void)hipStreamSynchronize(e->s_out);
     (void)hipStreamSynchronize(e->s_in);
     if (e->st_out.kstream) (void)hipStreamSynchronize(e->st_out.kstream);
@@ -1018,6 +1034,85 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double
     (void)hipDeviceSynchronize();
     cleanup();
     return rc;
+}
+
+int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes, int32_t max_wgs)
+{
+    if (!e || list_bad(ids, n) || passes < 1 || passes > 256 || max_wgs < 0) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    if (e->read_passes != 0) return KV_EINVAL;  // previous reader not waited for
+    if (out_of_range(ids, n, e->cfg.n_hbm_blocks)) return KV_ERANGE;
+    if (n > e->cfg.n_hbm_blocks) return KV_EINVAL;
+    if (e->seg % 16 != 0 || ((uintptr_t)e->hbm & 15u) != 0) return KV_EUNSUP;
+    if (!e->s_read) {
+        const size_t idb = (size_t)e->cfg.n_hbm_blocks * sizeof(int32_t);
+        if (hipMalloc((void **)&e->read_ids, idb) != hipSuccess ||
+            hipHostMalloc((void **)&e->read_ids_host, idb, hipHostMallocDefault) != hipSuccess ||
+            hipMalloc((void **)&e->read_acc, sizeof(unsigned long long)) != hipSuccess ||
+            hipHostMalloc((void **)&e->read_acc_host, sizeof(unsigned long long), hipHostMallocDefault) !=
+                hipSuccess) {
+            (void)hipGetLastError();
+            return KV_ENOMEM;
+        }
+        HIPTRY(e, hipStreamCreateWithFlags(&e->s_read, hipStreamNonBlocking));
+    }
+    while ((int32_t)e->read_ev.size() < passes + 1) {
+        hipEvent_t x;
+        HIPTRY(e, hipEventCreate(&x));
+        e->read_ev.push_back(x);
+    }
+    constexpr int U = 8;
+    dkv::ReadParams p{};
+    p.hbm = e->hbm;
+    p.ids = e->read_ids;
+    p.acc = e->read_acc;
+    p.seg_bytes = e->seg;
+    p.hbm_plane_stride = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    p.n = (uint32_t)n;
+    p.n_planes = e->n_planes;
+    p.vec_per_seg = (uint32_t)(e->seg / 16);
+    p.tiles_per_seg = (p.vec_per_seg + dkv::kThreads * U - 1) / (dkv::kThreads * U);
+    if (!dir_tiles(p.n, p.n_planes, p.tiles_per_seg, p.tiles)) return KV_EUNSUP;
+    *e->read_acc_host = 0;
+    HIPTRY(e, hipMemsetAsync(e->read_acc, 0, sizeof(unsigned long long), e->s_read));
+    if (n > 0) {
+        memcpy(e->read_ids_host, ids, (size_t)n * sizeof(int32_t));
+        HIPTRY(e, hipMemcpyAsync(e->read_ids, e->read_ids_host, (size_t)n * sizeof(int32_t),
+                                 hipMemcpyHostToDevice, e->s_read));
+    }
+    int wgs = 16 * (e->n_cus > 0 ? e->n_cus : 256);
+    if (max_wgs > 0) wgs = std::min(wgs, (int)max_wgs);
+    wgs = (int)std::min<uint32_t>((uint32_t)wgs, std::max<uint32_t>(p.tiles, 1u));
+    HIPTRY(e, hipEventRecord(e->read_ev[0], e->s_read));
+    for (int32_t k = 0; k < passes; k++) {
+        if (p.tiles > 0) {
+            hipLaunchKernelGGL((dkv::kv_reader_kernel<U>), dim3((unsigned)wgs), dim3(dkv::kThreads), 0, e->s_read, p);
+            HIPTRY(e, hipGetLastError());
+        }
+        HIPTRY(e, hipEventRecord(e->read_ev[(size_t)k + 1], e->s_read));
+    }
+    HIPTRY(e, hipMemcpyAsync(e->read_acc_host, e->read_acc, sizeof(unsigned long long), hipMemcpyDeviceToHost,
+                             e->s_read));
+    e->read_passes = passes;
+    return KV_OK;
+}
+
+int kv_reader_wait(kv_engine *e, uint64_t *checksum, double *ms_per_pass)
+{
+    if (!e || !checksum) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    if (e->read_passes == 0) return KV_EINVAL;
+    HIPTRY(e, hipStreamSynchronize(e->s_read));
+    *checksum = (uint64_t)*e->read_acc_host;
+    if (ms_per_pass) {
+        for (int32_t k = 0; k < e->read_passes; k++) {
+            float ms = 0;
+            HIPTRY(e, hipEventElapsedTime(&ms, e->read_ev[(size_t)k], e->read_ev[(size_t)k + 1]));
+            ms_per_pass[k] = ms;
+        }
+    }
+    e->read_passes = 0;
+    return KV_OK;
 }
 
 const char *kv_strerror(int code)

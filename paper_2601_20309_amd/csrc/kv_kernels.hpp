@@ -149,4 +149,52 @@ __global__ __launch_bounds__(kThreads) void kv_move_kernel(const MoveParams p)
     }
 }
 
+// Synthetic decode reader: streams every segment of the named blocks, plane by
+// plane (layer-major, as attention over the running requests would), and adds
+// up all 32-bit words modulo 2^64.  HBM-bound; read-only.  One tile is
+// kThreads * U 16-byte vectors of one segment; tiles are dealt round-robin so
+// neighbouring workgroups (which sit on different XCDs) stream neighbouring
+// 4 KiB * U pieces and every HBM channel stays busy.
+struct ReadParams {
+    const uint8_t *hbm;
+    const int32_t *ids;
+    unsigned long long *acc;  // one 64-bit accumulator in device memory
+    uint64_t seg_bytes;
+    uint64_t hbm_plane_stride;
+    uint32_t n;              // blocks
+    uint32_t n_planes;
+    uint32_t vec_per_seg;    // seg_bytes / 16
+    uint32_t tiles_per_seg;
+    uint32_t tiles;          // n * n_planes * tiles_per_seg
+};
+
+template <int U>
+__global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
+{
+    const uint32_t tid = threadIdx.x;
+    unsigned long long sum = 0;
+    for (uint32_t t = blockIdx.x; t < p.tiles; t += gridDim.x) {
+        const uint32_t segidx = t / p.tiles_per_seg;
+        const uint32_t tin = t - segidx * p.tiles_per_seg;
+        const uint32_t pl = segidx / p.n;
+        const uint32_t i = segidx - pl * p.n;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(
+            p.hbm + (uint64_t)pl * p.hbm_plane_stride + (uint64_t)(uint32_t)p.ids[i] * p.seg_bytes);
+        const uint32_t v0 = tin * (kThreads * U) + tid;
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const uint32_t vi = v0 + u * kThreads;
+            v[u] = vi < p.vec_per_seg ? src[vi] : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            sum += (unsigned long long)v[u].x + v[u].y + (unsigned long long)v[u].z + v[u].w;
+    }
+    // wave reduction, then one atomic per wave
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_down(sum, off, 64);
+    if ((tid & 63u) == 0) atomicAdd(p.acc, sum);
+}
+
 }  // namespace dkv

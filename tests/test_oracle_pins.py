@@ -416,3 +416,40 @@ def test_offsets_are_a_bijection_onto_the_images():
              for sl in range(sh.n_host_slots)}
         assert h == set(range(0, O.cache_bytes(s), seg))
         assert p == set(range(0, O.pool_bytes(s), seg))
+
+
+# ---- decode reader checksum ----
+
+@pytest.mark.parametrize("name", ["tiny", "ragged"])
+def test_read_checksum_against_numpy_and_closed_form(name):
+    sh = W.SHAPES[name]
+    s = O.shape_of(sh)
+    rot = W.config_rotation(name)
+    cache, _ = V.make_images(sh, O.BLOCK_FIRST, rot, 9)
+    ids = np.concatenate([rot.out_ids, rot.in_ids])
+    rc, got = O.read_checksum(s, u8(cache), ids)
+    assert rc == O.OK
+    # library routine: gather the blocks by indexing, view as little-endian words, sum
+    blocks = np.ascontiguousarray(V.hbm_view(sh, cache)[:, :, ids])
+    want = int(blocks.view("<u4").sum(dtype=np.uint64))
+    assert got == want
+    # closed form: a constant fill makes the sum words x constant (and it wraps mod 2^64)
+    const = np.full_like(cache, 0xFFFF)
+    rc, got = O.read_checksum(s, u8(const), ids)
+    words = len(ids) * O.block_bytes(s) // 4
+    assert got == (words * 0xFFFFFFFF) % (1 << 64)
+    # one flipped bit anywhere in a named block moves the sum by exactly that bit
+    c2 = cache.copy()
+    V.hbm_view(sh, c2)[sh.n_layers - 1, 1, int(ids[-1]), sh.block_size - 1, 0, 1] ^= 0x0100
+    rc, got2 = O.read_checksum(s, u8(c2), ids)
+    rc, got1 = O.read_checksum(s, u8(cache), ids)
+    assert (got2 - got1) % (1 << 64) in (0x0100_0000 % (1 << 64), (-0x0100_0000) % (1 << 64))
+    # an un-named block does not enter
+    other = next(b for b in range(sh.n_hbm_blocks) if b not in set(ids.tolist()))
+    c3 = cache.copy(); V.hbm_view(sh, c3)[:, :, other] ^= 0xFFFF
+    assert O.read_checksum(s, u8(c3), ids)[1] == got1
+    # a block named twice counts twice; order does not matter; empty list sums to 0
+    rc, twice = O.read_checksum(s, u8(cache), np.concatenate([ids, ids[::-1]]))
+    assert twice == (2 * got1) % (1 << 64)
+    assert O.read_checksum(s, u8(cache), [])[1] == 0
+    assert O.read_checksum(s, u8(cache), [sh.n_hbm_blocks])[0] == O.ERANGE
