@@ -72,7 +72,7 @@ typedef struct {
     int32_t chunk_layers;  /* layers per pipeline chunk; 0 = engine picks */
     int32_t max_copy_wgs;  /* workgroups a copy kernel may occupy; 0 = engine picks */
     int32_t vecs_per_lane; /* 16-byte vectors each lane keeps in flight per direction in the link kernels: 0 = engine picks, else 1, 2, 4 or 8 */
-    uint64_t staging_bytes;/* SDMA_STAGED: bytes of HBM staging per direction (double-buffered inside); 0 = engine picks */
+    uint64_t staging_bytes;/* SDMA_STAGED: bytes of HBM staging per direction = largest chunk; 0 = engine picks (256 MiB) */
 } kv_config;
 
 typedef struct {

@@ -7,9 +7,9 @@
 //   ZEROCOPY     the same kernel once per direction on the two streams.
 //                Default for kv_swap_out / kv_swap_in.
 //   SDMA_STAGED  pack kernel -> HBM staging -> hipMemcpyAsync per contiguous
-//                host run (DMA engines), and the mirror; chunks are double
-//                buffered so pack(c+1) overlaps copy(c) and copy(c+1) overlaps
-//                unpack(c).  Uses no compute units for the link itself.
+//                host run (DMA engines), and the mirror, chunk after chunk, each
+//                direction in order on its own stream.  Uses no compute units
+//                for the link itself.
 //   NAIVE        one hipMemcpyAsync per segment, the per-segment baseline of
 //                Section 4.3.1 of the paper, kept for the benchmark ladder.
 #include <hip/hip_runtime.h>
@@ -112,16 +112,7 @@ int admit(const kv_config *c, Marks &mk, const int32_t *oi, const int32_t *os, i
     return KV_OK;
 }
 
-constexpr int kRing = 8;       // descriptor sets that may be in flight
-constexpr int kStageBufs = 2;  // double buffering of staging chunks
-
-struct StageDir {
-    uint8_t *buf[kStageBufs] = {nullptr, nullptr};
-    hipEvent_t kernel_done[kStageBufs] = {nullptr, nullptr};  // pack / unpack finished with buf
-    hipEvent_t copy_done[kStageBufs] = {nullptr, nullptr};    // DMA finished with buf
-    bool used[kStageBufs] = {false, false};
-    hipStream_t kstream = nullptr;                            // pack / unpack kernels
-};
+constexpr int kRing = 8;  // descriptor sets that may be in flight
 
 }  // namespace
 
@@ -160,8 +151,10 @@ struct kv_engine {
     kv_stats acc{}, last{};
     int sticky = KV_OK;
 
-    // staging for SDMA_STAGED
-    StageDir st_out, st_in;
+    // staging for SDMA_STAGED: one buffer per direction, chunk_cap bytes each.
+    // A direction's pack / copy / unpack all run in order on that direction's
+    // stream, so a buffer is never reused before its last reader is done.
+    uint8_t *stage_out = nullptr, *stage_in = nullptr;
     uint64_t chunk_cap = 0;
 
     // synthetic decode reader
@@ -581,20 +574,17 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
         if (rc != KV_OK) return rc;
         sorted_desc(e, ii, is, ni, h_in);
     }
-    StageDir &so = e->st_out, &si = e->st_in;
     if (no > 0) {
-        // pack kernels run on their own stream, after whatever stream_out already holds
         HIPTRY(e, hipMemcpyAsync(d_out, h_out, 2 * (size_t)no * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
-        HIPTRY(e, hipEventRecord(e->ev_join, e->s_out));
-        HIPTRY(e, hipStreamWaitEvent(so.kstream, e->ev_join, 0));
     }
     if (ni > 0) {
         HIPTRY(e, hipMemcpyAsync(d_in, h_in, 2 * (size_t)ni * sizeof(int32_t), hipMemcpyHostToDevice, e->s_in));
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
     }
-    // chunk lists, enumerated in the same order for both directions and interleaved
-    struct Cur { uint32_t j0 = 0, p0 = 0; bool done = true; int c = 0; } co, ci;
+    // Chunks of the two directions are enqueued alternately so both streams fill
+    // together.  out: pack(c) then its copies; in: copies of c then unpack(c).
+    struct Cur { uint32_t j0 = 0, p0 = 0; bool done = true; } co, ci;
     co.done = no == 0;
     ci.done = ni == 0;
     int32_t n_ops = 0;
@@ -602,22 +592,15 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
         if (!co.done) {
             const uint32_t j1 = std::min<uint32_t>(co.j0 + po.blocks_per_chunk, (uint32_t)no);
             const uint32_t p1 = std::min<uint32_t>(co.p0 + po.planes_per_chunk, e->n_planes);
-            const int b = co.c % kStageBufs;
-            if (so.used[b]) HIPTRY(e, hipStreamWaitEvent(so.kstream, so.copy_done[b], 0));
-            MoveParams p = stage_params(e, so.buf[b], j1 - co.j0, co.p0, p1 - co.p0, U);
+            MoveParams p = stage_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, U);
             p.out = DirDesc{d_out + co.j0, nullptr, j1 - co.j0, 0};
             if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.out.tiles);
-            launch_move(U, e->vec, wgs, so.kstream, p);
+            launch_move(U, e->vec, wgs, e->s_out, p);
             HIPTRY(e, hipGetLastError());
-            HIPTRY(e, hipEventRecord(so.kernel_done[b], so.kstream));
-            HIPTRY(e, hipStreamWaitEvent(e->s_out, so.kernel_done[b], 0));
-            if (chunk_copies(e, true, so.buf[b], h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
+            if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
                 return KV_EHIP;
-            HIPTRY(e, hipEventRecord(so.copy_done[b], e->s_out));
-            so.used[b] = true;
             n_ops++;
-            co.c++;
             co.p0 = p1;
             if (co.p0 >= e->n_planes) { co.p0 = 0; co.j0 = j1; }
             co.done = co.j0 >= (uint32_t)no;
@@ -625,56 +608,38 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
         if (!ci.done) {
             const uint32_t j1 = std::min<uint32_t>(ci.j0 + pi.blocks_per_chunk, (uint32_t)ni);
             const uint32_t p1 = std::min<uint32_t>(ci.p0 + pi.planes_per_chunk, e->n_planes);
-            const int b = ci.c % kStageBufs;
-            if (si.used[b]) HIPTRY(e, hipStreamWaitEvent(e->s_in, si.kernel_done[b], 0));
-            if (chunk_copies(e, false, si.buf[b], h_in + ni, ci.j0, j1, ci.p0, p1, e->s_in, n_ops) != KV_OK)
+            if (chunk_copies(e, false, e->stage_in, h_in + ni, ci.j0, j1, ci.p0, p1, e->s_in, n_ops) != KV_OK)
                 return KV_EHIP;
-            HIPTRY(e, hipEventRecord(si.copy_done[b], e->s_in));
-            HIPTRY(e, hipStreamWaitEvent(si.kstream, si.copy_done[b], 0));
-            MoveParams p = stage_params(e, si.buf[b], j1 - ci.j0, ci.p0, p1 - ci.p0, U);
+            MoveParams p = stage_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, U);
             p.in = DirDesc{d_in + ci.j0, nullptr, j1 - ci.j0, 0};
             if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.in.tiles);
-            launch_move(U, e->vec, wgs, si.kstream, p);
+            launch_move(U, e->vec, wgs, e->s_in, p);
             HIPTRY(e, hipGetLastError());
-            HIPTRY(e, hipEventRecord(si.kernel_done[b], si.kstream));
-            si.used[b] = true;
             n_ops++;
-            ci.c++;
             ci.p0 = p1;
             if (ci.p0 >= e->n_planes) { ci.p0 = 0; ci.j0 = j1; }
             ci.done = ci.j0 >= (uint32_t)ni;
         }
     }
     if (no > 0 && mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
-    if (ni > 0) {
-        // stream_in has to see the last unpack kernels
-        for (int b = 0; b < kStageBufs; b++)
-            if (si.used[b]) HIPTRY(e, hipStreamWaitEvent(e->s_in, si.kernel_done[b], 0));
-        if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
-    }
+    if (ni > 0 && mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
     e->acc.n_launches += n_ops;
     return KV_OK;
 }
 
 int ensure_staging(kv_engine *e)
 {
-    if (e->st_out.buf[0]) return KV_OK;
-    uint64_t per_dir = e->cfg.staging_bytes ? e->cfg.staging_bytes : (128ull << 20);
-    uint64_t cap = per_dir / kStageBufs;
+    if (e->stage_out) return KV_OK;
+    // 256 MiB chunks keep the kernel <-> copy hand-overs (tens of microseconds
+    // each) under 1 % of a chunk's link time
+    uint64_t cap = e->cfg.staging_bytes ? e->cfg.staging_bytes : (256ull << 20);
     cap -= cap % 256;
     if (cap < 2 * e->seg) return KV_EINVAL;
     e->chunk_cap = cap;
-    for (StageDir *d : {&e->st_out, &e->st_in}) {
-        for (int b = 0; b < kStageBufs; b++) {
-            if (hipMalloc((void **)&d->buf[b], cap) != hipSuccess) {
-                (void)hipGetLastError();
-                return KV_ENOMEM;
-            }
-            HIPTRY(e, hipEventCreateWithFlags(&d->kernel_done[b], hipEventDisableTiming));
-            HIPTRY(e, hipEventCreateWithFlags(&d->copy_done[b], hipEventDisableTiming));
-        }
-        HIPTRY(e, hipStreamCreateWithFlags(&d->kstream, hipStreamNonBlocking));
+    if (hipMalloc((void **)&e->stage_out, cap) != hipSuccess || hipMalloc((void **)&e->stage_in, cap) != hipSuccess) {
+        (void)hipGetLastError();
+        return KV_ENOMEM;
     }
     return KV_OK;
 }
@@ -728,14 +693,8 @@ void free_engine(kv_engine *e)
     auto ev = [](hipEvent_t &x) { if (x) { (void)hipEventDestroy(x); x = nullptr; } };
     for (int k = 0; k < kRing; k++) { ev(e->ring_out[k]); ev(e->ring_in[k]); }
     ev(e->ev_o0); ev(e->ev_o1); ev(e->ev_i0); ev(e->ev_i1); ev(e->ev_join);
-    for (StageDir *d : {&e->st_out, &e->st_in}) {
-        for (int b = 0; b < kStageBufs; b++) {
-            if (d->buf[b]) (void)hipFree(d->buf[b]);
-            ev(d->kernel_done[b]);
-            ev(d->copy_done[b]);
-        }
-        if (d->kstream) (void)hipStreamDestroy(d->kstream);
-    }
+    if (e->stage_out) (void)hipFree(e->stage_out);
+    if (e->stage_in) (void)hipFree(e->stage_in);
     if (e->s_read) (void)hipStreamDestroy(e->s_read);
     if (e->read_ids) (void)hipFree(e->read_ids);
     if (e->read_ids_host) (void)hipHostFree(e->read_ids_host);
@@ -897,8 +856,6 @@ int kv_destroy(kv_engine *e)
     if (e->s_read) (void)hipStreamSynchronize(e->s_read);
     (void)hipStreamSynchronize(e->s_out);
     (void)hipStreamSynchronize(e->s_in);
-    if (e->st_out.kstream) (void)hipStreamSynchronize(e->st_out.kstream);
-    if (e->st_in.kstream) (void)hipStreamSynchronize(e->st_in.kstream);
     free_engine(e);
     return KV_OK;
 }
@@ -923,9 +880,7 @@ int kv_wait(kv_engine *e)
 {
     if (!e) return KV_EINVAL;
     if (e->sticky != KV_OK) return e->sticky;
-    // Only streams this engine put work on are waited for.  Everything the
-    // staging streams do is ordered before the last event on stream_out /
-    // stream_in, so those two cover it.
+    // Only streams this engine put work on are waited for.
     for (int side = 0; side < 2; side++) {
         const bool pending = side == 0 ? e->out_pending : e->in_pending;
         if (!pending) continue;
@@ -933,8 +888,6 @@ int kv_wait(kv_engine *e)
     }
     e->out_pending = e->in_pending = false;
     for (int k = 0; k < kRing; k++) e->ring_out_rec[k] = e->ring_in_rec[k] = false;
-    for (StageDir *d : {&e->st_out, &e->st_in})
-        for (int b = 0; b < kStageBufs; b++) d->used[b] = false;
     if (e->batch_open) {
         e->acc.ms_e2e = now_ms() - e->t0;
         float ms = 0;

@@ -1,0 +1,234 @@
+"""Measurements beyond bench.py's headline line, on one MI355X:
+
+  python -m paper_2601_20309_amd.experiments ladder        # analogue of the paper's Table 2
+  python -m paper_2601_20309_amd.experiments configs       # configs[1..3] of the benchmark spec, default path
+  python -m paper_2601_20309_amd.experiments interference  # configs[4]: rotation beside a decode reader
+
+Each prints a markdown table.  Correctness of every path measured here is
+covered by the GPU tests; these runs only time.
+"""
+from __future__ import annotations
+
+import statistics
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workloads as W
+
+
+def _cache(shape):
+    # contents do not matter to a timing run; N(0,1) bf16 all the same
+    c = torch.empty(shape.cache_dims(), dtype=torch.bfloat16, device="cuda").normal_()
+    torch.cuda.synchronize()
+    return c
+
+
+def _time_calls(eng, fn, reps, warm=2):
+    """Median wall ms and stats of `fn` (which must end in kv_wait)."""
+    ts, ko, ki = [], [], []
+    for i in range(warm + reps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(i)
+        dt = (time.perf_counter() - t0) * 1e3
+        if i >= warm:
+            st = eng.kv_last_stats()
+            ts.append(dt); ko.append(st["ms_out"]); ki.append(st["ms_in"])
+    return statistics.median(ts), statistics.median(ko), statistics.median(ki)
+
+
+def _rot_calls(eng, rot):
+    inv = rot.inverse()
+    return (eng.prepare(rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots),
+            eng.prepare(inv.out_ids, inv.out_slots, inv.in_ids, inv.in_slots))
+
+
+def ladder(name="qwen25_32b"):
+    """Naive -> per-block DMA -> one kernel per direction (serial) -> duplex, as in
+    Table 2 of the paper (which ran 8 GB each way of Qwen2.5-32B KV on GH200)."""
+    shape = W.SHAPES[name]
+    link = B.kv_probe_link(256 << 20, 5)
+    cache = _cache(shape)
+    rot = W.config_rotation(name)
+    inv = rot.inverse()
+    blk = None
+    rows = []
+
+    def run(label, path, serial, reps, contiguous=False, layout=B.KV_HOST_BLOCK_FIRST):
+        nonlocal blk
+        r = W.config_rotation(name, contiguous_slots=contiguous)
+        ri = r.inverse()
+        eng = B.Engine(B.make_config(shape, layout, path), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        nbytes = len(r.out_ids) * blk
+        if serial:
+            t_out, t_in = [], []
+            for i in range(reps + 1):
+                a, b = (r, ri) if i % 2 == 0 else (ri, r)
+                torch.cuda.synchronize(); t0 = time.perf_counter()
+                assert eng.kv_swap_out(a.out_ids, a.out_slots) == 0 and eng.kv_wait() == 0
+                t1 = time.perf_counter()
+                assert eng.kv_swap_in(a.in_slots, a.in_ids) == 0 and eng.kv_wait() == 0
+                t2 = time.perf_counter()
+                if i >= 1:
+                    t_out.append((t1 - t0) * 1e3); t_in.append((t2 - t1) * 1e3)
+            mo, mi = statistics.median(t_out), statistics.median(t_in)
+            rows.append((label, nbytes / mo / 1e6, "u", nbytes / mi / 1e6, "u", mo + mi))
+        else:
+            calls = _rot_calls(eng, r)
+
+            def fn(i):
+                assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+            ms, ko, ki = _time_calls(eng, fn, reps)
+            rows.append((label, nbytes / ms / 1e6, "b", nbytes / ms / 1e6, "b", ms))
+        eng.kv_destroy()
+        print(f"  done: {label}", file=sys.stderr, flush=True)
+
+    run("Naive: one hipMemcpyAsync per segment", B.KV_PATH_NAIVE, True, 1)
+    run("MS analogue: pack kernel + one DMA copy per block", B.KV_PATH_SDMA_STAGED, True, 3)
+    run("MS+MK analogue: one zero-copy kernel per direction, serial", B.KV_PATH_ZEROCOPY, True, 3)
+    run("DMA staged, consecutive slots, both directions at once", B.KV_PATH_SDMA_STAGED, False, 3, contiguous=True)
+    run("Two zero-copy kernels on two streams", B.KV_PATH_ZEROCOPY, False, 3)
+    run("Fused duplex kernel (default)", B.KV_PATH_FUSED, False, 5)
+    nbytes = len(rot.out_ids) * blk
+    rows.append(("Ceiling: hipMemcpyAsync pinned, one way at a time", link["d2h"], "u", link["h2d"], "u",
+                 nbytes / link["d2h"] / 1e6 + nbytes / link["h2d"] / 1e6))
+    rows.append(("Ceiling: hipMemcpyAsync pinned, both ways at once", link["d2h_duplex"], "b",
+                 link["h2d_duplex"], "b", nbytes / link["d2h_duplex"] / 1e6))
+    print(f"\nLadder on {name}: {len(rot.out_ids)} blocks x {blk >> 20} MiB = {nbytes / 2**30:.1f} GiB per direction, "
+          f"scattered block ids and slots\n")
+    print("| Method | D2H GB/s | H2D GB/s | E2E ms |")
+    print("|---|---|---|---|")
+    for label, d, du, h, hu, ms in rows:
+        print(f"| {label} | {d:.2f} ({du}) | {h:.2f} ({hu}) | {ms:.2f} |")
+
+
+def configs():
+    link = B.kv_probe_link(256 << 20, 5)
+    print(f"\nhipMemcpyAsync pinned peaks: D2H {link['d2h']:.2f}, H2D {link['h2d']:.2f}, both at once "
+          f"{link['d2h_duplex']:.2f} per direction (GB/s)\n")
+    print("| Config | path | out GiB | in GiB | step ms | out GB/s | in GB/s | % of D2H peak | % of H2D peak | launches |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    plans = [
+        ("llama3_8b", dict(), "default"),
+        ("llama3_8b", dict(host_layout=B.KV_HOST_LAYER_FIRST), "layer-first pool"),
+        ("batch", dict(), "default"),
+        ("long70b", dict(), "default (one launch)"),
+        ("long70b", dict(path=B.KV_PATH_SDMA_STAGED, host_layout=B.KV_HOST_LAYER_FIRST, chunk_layers=1,
+                         staging_bytes=512 << 20), "DMA staged, per-layer chunks, consecutive slots"),
+    ]
+    cache, cache_name = None, None
+    for name, kw, label in plans:
+        shape = W.SHAPES[name]
+        if cache_name != (shape.cache_dims()):
+            del cache
+            torch.cuda.empty_cache()
+            cache, cache_name = _cache(shape), shape.cache_dims()
+        contiguous = kw.get("path") == B.KV_PATH_SDMA_STAGED
+        rot = W.config_rotation(name, contiguous_slots=contiguous)
+        eng = B.Engine(B.make_config(shape, **kw), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        calls = _rot_calls(eng, rot)
+
+        def fn(i):
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+        ms, ko, ki = _time_calls(eng, fn, 6 if name == "llama3_8b" else 4)
+        st = eng.kv_last_stats()
+        bo, bi = len(rot.out_ids) * blk, len(rot.in_ids) * blk
+        go, gi = bo / ms / 1e6, bi / ms / 1e6
+        print(f"| {name} | {label} ({B.PATH_NAMES[st['path_used']]}) | {bo / 2**30:.2f} | {bi / 2**30:.2f} | {ms:.3f} | "
+              f"{go:.2f} | {gi:.2f} | {100 * go / link['d2h']:.1f} | {100 * gi / link['h2d']:.1f} | {st['n_launches']} |",
+              flush=True)
+        eng.kv_destroy()
+    # configs[2] again as 32 back-to-back calls, one request pair each
+    shape = W.SHAPES["batch"]
+    del cache
+    torch.cuda.empty_cache()
+    cache = _cache(shape)
+    info = W.batch_rotation(shape, W.BASE_SEED + 102)
+    rot = info["rotation"]; bo_, bi_ = info["bounds_out"], info["bounds_in"]
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    pairs_f, pairs_b = [], []
+    inv = rot.inverse()
+    for r in range(len(bo_) - 1):
+        o, i_ = slice(bo_[r], bo_[r + 1]), slice(bi_[r], bi_[r + 1])
+        pairs_f.append(eng.prepare(rot.out_ids[o], rot.out_slots[o], rot.in_ids[i_], rot.in_slots[i_]))
+        pairs_b.append(eng.prepare(inv.out_ids[i_], inv.out_slots[i_], inv.in_ids[o], inv.in_slots[o]))
+
+    def fn(i):
+        for c in (pairs_f if i % 2 == 0 else pairs_b):
+            assert c() == 0
+        assert eng.kv_wait() == 0
+    ms, ko, ki = _time_calls(eng, fn, 4)
+    bo, bi = len(rot.out_ids) * blk, len(rot.in_ids) * blk
+    print(f"| batch | default, {len(pairs_f)} calls of one request pair each, one kv_wait | {bo / 2**30:.2f} | {bi / 2**30:.2f} | "
+          f"{ms:.3f} | {bo / ms / 1e6:.2f} | {bi / ms / 1e6:.2f} | {100 * bo / ms / 1e6 / link['d2h']:.1f} | "
+          f"{100 * bi / ms / 1e6 / link['h2d']:.1f} | {eng.kv_last_stats()['n_launches']} |")
+    eng.kv_destroy()
+
+
+def interference():
+    """configs[4]: 8 x 4096-token requests each way while a reader streams the KV
+    of 19200 other blocks (37.5 GiB) layer by layer."""
+    name = "interference"
+    shape = W.SHAPES[name]
+    link = B.kv_probe_link(256 << 20, 5)
+    cache = _cache(shape)
+    print(f"\nhipMemcpyAsync pinned peaks: D2H {link['d2h']:.2f}, H2D {link['h2d']:.2f} GB/s\n")
+    print("| rotation path | copy WGs | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
+          "reader alone TB/s | reader beside rotation TB/s |")
+    print("|---|---|---|---|---|---|")
+    for path, wgs, contiguous in [(B.KV_PATH_FUSED, 0, False), (B.KV_PATH_FUSED, 32, False),
+                                  (B.KV_PATH_FUSED, 16, False), (B.KV_PATH_SDMA_STAGED, 0, True)]:
+        rot = W.config_rotation(name, contiguous_slots=contiguous)
+        named = np.zeros(shape.n_hbm_blocks, bool)
+        named[rot.out_ids] = True; named[rot.in_ids] = True
+        others = np.flatnonzero(~named)[:19200].astype(np.int32)
+        eng = B.Engine(B.make_config(shape, path=path, max_copy_wgs=wgs), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        calls = _rot_calls(eng, rot)
+        moved = (len(rot.out_ids) + len(rot.in_ids)) * blk
+        read_bytes = len(others) * blk
+
+        def alone(i):
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+        ms_alone, _, _ = _time_calls(eng, alone, 4)
+        # reader alone
+        assert eng.kv_reader_start(others, 6) == 0
+        rc, _, pm = eng.kv_reader_wait()
+        read_alone = read_bytes / statistics.median(pm[1:]) / 1e9
+        # both: enough reader passes to outlast the rotation
+        n_pass = min(256, int(ms_alone / statistics.median(pm[1:]) * 1.5) + 4)
+        both = []
+        read_both = []
+        for i in range(4):
+            torch.cuda.synchronize()
+            assert eng.kv_reader_start(others, n_pass) == 0
+            t0 = time.perf_counter()
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+            dt = (time.perf_counter() - t0) * 1e3
+            rc, _, pm2 = eng.kv_reader_wait()
+            assert rc == 0
+            if i >= 1:
+                both.append(dt)
+                # passes that ran entirely inside the rotation window
+                acc, inside = 0.0, []
+                for p in pm2:
+                    if acc + p <= dt:
+                        inside.append(p)
+                    acc += p
+                read_both.append(read_bytes / statistics.median(inside[1:] or pm2) / 1e9)
+        ms_both = statistics.median(both)
+        print(f"| {B.PATH_NAMES[path]} | {wgs or 'default'} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
+              f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
+        eng.kv_destroy()
+
+
+if __name__ == "__main__":
+    what = sys.argv[1] if len(sys.argv) > 1 else "configs"
+    {"ladder": ladder, "configs": configs, "interference": interference}[what]()
