@@ -72,6 +72,8 @@ typedef struct {
     int32_t chunk_layers;  /* layers per pipeline chunk; 0 = engine picks */
     int32_t max_copy_wgs;  /* workgroups a copy kernel may occupy; 0 = engine picks */
     int32_t vecs_per_lane; /* 16-byte vectors each lane keeps in flight per direction in the link kernels: 0 = engine picks, else 1, 2, 4 or 8 */
+    int32_t wg_lanes;      /* lanes per workgroup of the link kernels: 0 = engine picks, else a multiple of 64 up to 1024 */
+    int32_t reserved;      /* must be 0 */
     uint64_t staging_bytes;/* SDMA_STAGED: bytes of HBM staging per direction = largest chunk; 0 = engine picks (256 MiB) */
 } kv_config;
 
@@ -176,7 +178,7 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d,
  * that it overlaps kv_rotate, and reduces what it read to the sum modulo 2^64
  * of all little-endian 32-bit words (a block named twice counts twice).  Read
  * only.  Needs segments that are multiples of 16 bytes (KV_EUNSUP otherwise).
- * max_wgs caps its workgroups (0 = engine picks).  One reader at a time:
+ * max_wgs caps its persistent workgroups (0 = engine picks).  One reader at a time:
  * kv_reader_wait() must come before the next kv_reader_start().
  */
 int kv_reader_start(kv_engine *engine, const int32_t *block_ids, int32_t n, int32_t passes, int32_t max_wgs);

@@ -31,7 +31,7 @@ EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", 
 class kv_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes", "n_hbm_blocks",
-        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "vecs_per_lane")] + \
+        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "vecs_per_lane", "wg_lanes", "reserved")] + \
         [("staging_bytes", C.c_uint64)]
 
 
@@ -90,11 +90,11 @@ lib = _load()
 
 
 def make_config(shape, host_layout=KV_HOST_BLOCK_FIRST, path=KV_PATH_AUTO, chunk_layers=0,
-                max_copy_wgs=0, staging_bytes=0, vecs_per_lane=0) -> kv_config:
+                max_copy_wgs=0, staging_bytes=0, vecs_per_lane=0, wg_lanes=0) -> kv_config:
     """kv_config from any object carrying the KV shape attributes."""
     return kv_config(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
                      shape.elem_bytes, shape.n_hbm_blocks, shape.n_host_slots, host_layout, path,
-                     chunk_layers, max_copy_wgs, vecs_per_lane, staging_bytes)
+                     chunk_layers, max_copy_wgs, vecs_per_lane, wg_lanes, 0, staging_bytes)
 
 
 def _ids(a):

@@ -48,6 +48,8 @@ bool config_ok(const kv_config *c)
     if (c->vecs_per_lane != 0 && c->vecs_per_lane != 1 && c->vecs_per_lane != 2 && c->vecs_per_lane != 4 &&
         c->vecs_per_lane != 8)
         return false;
+    if (c->reserved != 0) return false;
+    if (c->wg_lanes < 0 || c->wg_lanes > dkv::kMaxThreads || c->wg_lanes % 64 != 0) return false;
     // sizes must stay far inside 64 bits
     const long double cache = 2.0L * c->n_layers * (long double)c->n_hbm_blocks * c->block_size *
                               c->n_kv_heads * c->head_dim * c->elem_bytes;
@@ -194,42 +196,51 @@ int pick_vec(const kv_engine *e)
     return 1;
 }
 
+// The four id arrays of a launch (device pointers; a direction that is not
+// used, or whose slots are the list indices, passes nullptr).
+struct MoveIds {
+    const int32_t *out_ids, *out_slots, *in_ids, *in_slots;
+};
+
 template <int U, bool NT>
-void launch_move_v(int vec, int wgs, hipStream_t s, const MoveParams &p)
+void launch_move_v(int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
 {
-    dim3 g((unsigned)wgs), b(dkv::kThreads);
+    dim3 g((unsigned)wgs), b((unsigned)lanes);
+#define DKV_LAUNCH(V) \
+    hipLaunchKernelGGL((dkv::kv_move_kernel<V, U, NT>), g, b, 0, s, p, d.out_ids, d.out_slots, d.in_ids, d.in_slots)
     switch (vec) {
-    case 16: hipLaunchKernelGGL((dkv::kv_move_kernel<dkv::u32x4, U, NT>), g, b, 0, s, p); break;
-    case 8: hipLaunchKernelGGL((dkv::kv_move_kernel<dkv::u32x2, U, NT>), g, b, 0, s, p); break;
-    case 4: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned int, U, NT>), g, b, 0, s, p); break;
-    case 2: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned short, U, NT>), g, b, 0, s, p); break;
-    default: hipLaunchKernelGGL((dkv::kv_move_kernel<unsigned char, U, NT>), g, b, 0, s, p); break;
+    case 16: DKV_LAUNCH(dkv::u32x4); break;
+    case 8: DKV_LAUNCH(dkv::u32x2); break;
+    case 4: DKV_LAUNCH(unsigned int); break;
+    case 2: DKV_LAUNCH(unsigned short); break;
+    default: DKV_LAUNCH(unsigned char); break;
     }
+#undef DKV_LAUNCH
 }
 
 bool g_nt = false;      // HBM-side non-temporal hint (measured: no gain on the link-bound path)
 
-void launch_move(int u, int vec, int wgs, hipStream_t s, const MoveParams &p)
+void launch_move(int u, int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
 {
     if (g_nt) {
         switch (u) {
-        case 1: launch_move_v<1, true>(vec, wgs, s, p); break;
-        case 2: launch_move_v<2, true>(vec, wgs, s, p); break;
-        case 4: launch_move_v<4, true>(vec, wgs, s, p); break;
-        default: launch_move_v<8, true>(vec, wgs, s, p); break;
+        case 1: launch_move_v<1, true>(vec, wgs, lanes, s, p, d); break;
+        case 2: launch_move_v<2, true>(vec, wgs, lanes, s, p, d); break;
+        case 4: launch_move_v<4, true>(vec, wgs, lanes, s, p, d); break;
+        default: launch_move_v<8, true>(vec, wgs, lanes, s, p, d); break;
         }
     } else {
         switch (u) {
-        case 1: launch_move_v<1, false>(vec, wgs, s, p); break;
-        case 2: launch_move_v<2, false>(vec, wgs, s, p); break;
-        case 4: launch_move_v<4, false>(vec, wgs, s, p); break;
-        default: launch_move_v<8, false>(vec, wgs, s, p); break;
+        case 1: launch_move_v<1, false>(vec, wgs, lanes, s, p, d); break;
+        case 2: launch_move_v<2, false>(vec, wgs, lanes, s, p, d); break;
+        case 4: launch_move_v<4, false>(vec, wgs, lanes, s, p, d); break;
+        default: launch_move_v<8, false>(vec, wgs, lanes, s, p, d); break;
         }
     }
 }
 
 // Fills the fields common to every launch; `u` = vectors per lane per tile.
-MoveParams base_params(const kv_engine *e, int u)
+MoveParams base_params(const kv_engine *e, int u, int lanes = dkv::kThreads)
 {
     MoveParams p{};
     p.hbm = e->hbm;
@@ -238,8 +249,9 @@ MoveParams base_params(const kv_engine *e, int u)
     p.plane0 = 0;
     p.n_planes = e->n_planes;
     p.vec_per_seg = (uint32_t)(e->seg / (uint64_t)e->vec);
-    const uint32_t tile = (uint32_t)dkv::kThreads * (uint32_t)u;
+    const uint32_t tile = (uint32_t)lanes * (uint32_t)u;
     p.tiles_per_seg = (p.vec_per_seg + tile - 1) / tile;
+    p.full_tiles = p.vec_per_seg % tile == 0 ? 1u : 0u;
     return p;
 }
 
@@ -320,17 +332,17 @@ int mark_end(kv_engine *e, bool out_side, int k, hipStream_t s)
 // Vectors per lane per tile for the link-bound launches.
 int link_u(const kv_engine *e)
 {
-    if (e->cfg.vecs_per_lane) return e->cfg.vecs_per_lane;
-    return (e->vec == 16 && e->seg >= 2u * dkv::kThreads * 16u) ? 2 : 1;
+    return e->cfg.vecs_per_lane ? e->cfg.vecs_per_lane : 1;
 }
 
-int default_wgs(const kv_engine *e, bool link_bound, int u = 1)
+int default_wgs(const kv_engine *e, bool link_bound)
 {
-    // Link-bound launches need few workgroups: 64 x 256 lanes x 2 x 16 B keeps
-    // 512 KiB in flight per direction, which saturates PCIe Gen5 x16 in both
-    // directions at once; more in flight only adds contention (measured).
+    // Link-bound launches need few workgroups: 96 x 256 lanes, each lane with
+    // two 16-byte vectors per direction in flight (the loop is pipelined one
+    // tile deep), is 768 KiB per direction, which saturates PCIe Gen5 x16 both
+    // ways at once; fewer leave gaps, more only add contention (measured).
     // HBM-bound pack / unpack launches want the whole chip.
-    int w = link_bound ? (u >= 2 ? 64 : 128) : 8 * (e->n_cus > 0 ? e->n_cus : 256);
+    int w = link_bound ? 96 : 8 * (e->n_cus > 0 ? e->n_cus : 256);
     if (e->cfg.max_copy_wgs > 0) w = link_bound ? (int)e->cfg.max_copy_wgs : std::min(w, (int)e->cfg.max_copy_wgs);
     return std::max(w, 1);
 }
@@ -341,20 +353,25 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
     int32_t *dd = e->desc_dev + (size_t)k * e->desc_cap;
     const int u = link_u(e);
-    MoveParams p = base_params(e, u);
+    const int lanes = e->cfg.wg_lanes ? e->cfg.wg_lanes : dkv::kThreads;
+    MoveParams p = base_params(e, u, lanes);
     p.far_out = e->pool;
     p.far_in = e->pool;
     pool_strides(e, p.far_slot_stride_out, p.far_plane_stride_out);
     p.far_slot_stride_in = p.far_slot_stride_out;
     p.far_plane_stride_in = p.far_plane_stride_out;
     p.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
-    DirDesc dout{dd, dd + no, (uint32_t)no, 0}, din{dd + 2 * (size_t)no, dd + 2 * (size_t)no + ni,
-                                                   (uint32_t)ni, 0};
+    int32_t *d_o = dd, *d_i = dd + 2 * (size_t)no;  // each: [ids | slots]
+    int32_t *h_o = dh, *h_i = dh + 2 * (size_t)no;
+    DirDesc dout{(uint32_t)no, 0, 0, 0}, din{(uint32_t)ni, 0, 0, 0};
+    const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
+    const MoveIds ids_both{d_o, d_o + no, d_i, d_i + ni};
     if (!dir_tiles((uint32_t)no, p.n_planes, p.tiles_per_seg, dout.tiles) ||
         !dir_tiles((uint32_t)ni, p.n_planes, p.tiles_per_seg, din.tiles))
         return KV_EUNSUP;
     const size_t ints_out = 2 * (size_t)no, ints_in = 2 * (size_t)ni;
-    const DirDesc none{nullptr, nullptr, 0, 0};
+    const DirDesc none{0, 0, 0, 0};
+    auto grid = [&](uint32_t tiles) { return (int)std::min<uint32_t>((uint32_t)default_wgs(e, true), tiles); };
 
     if (path == KV_PATH_FUSED && no > 0 && ni > 0) {
         // one launch on stream_out; stream_in is joined before (if it holds work) and after
@@ -363,7 +380,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
             e->in_dirty = false;
         }
-        HIPTRY(e, hipMemcpyAsync(dd, dh, (ints_out + ints_in) * sizeof(int32_t), hipMemcpyHostToDevice,
+        HIPTRY(e, hipMemcpyAsync(d_o, h_o, (ints_out + ints_in) * sizeof(int32_t), hipMemcpyHostToDevice,
                                  e->s_out));
         if (!e->b_o0 && !e->b_i0) {  // one start timestamp serves both directions
             if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
@@ -377,9 +394,8 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         }
         p.out = dout;
         p.in = din;
-        const uint32_t tiles = std::max(dout.tiles, din.tiles);
-        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true, u), tiles);
-        launch_move(u, e->vec, wgs, e->s_out, p);
+        const int wgs = grid(std::max(dout.tiles, din.tiles));
+        launch_move(u, e->vec, wgs, lanes, e->s_out, p, ids_both);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->b_i1 = e->ring_out[k];
@@ -389,24 +405,23 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     }
     // one kernel per direction, each on its own stream
     if (no > 0) {
-        HIPTRY(e, hipMemcpyAsync(dd, dh, ints_out * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
+        HIPTRY(e, hipMemcpyAsync(d_o, h_o, ints_out * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         p.out = dout;
         p.in = none;
-        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true, u), dout.tiles);
-        launch_move(u, e->vec, wgs, e->s_out, p);
+        const int wgs = grid(dout.tiles);
+        launch_move(u, e->vec, wgs, lanes, e->s_out, p, ids_out);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
     }
     if (ni > 0) {
-        HIPTRY(e, hipMemcpyAsync(dd + ints_out, dh + ints_out, ints_in * sizeof(int32_t),
-                                 hipMemcpyHostToDevice, e->s_in));
+        HIPTRY(e, hipMemcpyAsync(d_i, h_i, ints_in * sizeof(int32_t), hipMemcpyHostToDevice, e->s_in));
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         p.out = none;
         p.in = din;
-        const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, true, u), din.tiles);
-        launch_move(u, e->vec, wgs, e->s_in, p);
+        const int wgs = grid(din.tiles);
+        launch_move(u, e->vec, wgs, lanes, e->s_in, p, ids_in);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
@@ -593,10 +608,10 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             const uint32_t j1 = std::min<uint32_t>(co.j0 + po.blocks_per_chunk, (uint32_t)no);
             const uint32_t p1 = std::min<uint32_t>(co.p0 + po.planes_per_chunk, e->n_planes);
             MoveParams p = stage_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, U);
-            p.out = DirDesc{d_out + co.j0, nullptr, j1 - co.j0, 0};
+            p.out = DirDesc{j1 - co.j0, 0, 1, 0};
             if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.out.tiles);
-            launch_move(U, e->vec, wgs, e->s_out, p);
+            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_out, p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr});
             HIPTRY(e, hipGetLastError());
             if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
                 return KV_EHIP;
@@ -611,10 +626,10 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             if (chunk_copies(e, false, e->stage_in, h_in + ni, ci.j0, j1, ci.p0, p1, e->s_in, n_ops) != KV_OK)
                 return KV_EHIP;
             MoveParams p = stage_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, U);
-            p.in = DirDesc{d_in + ci.j0, nullptr, j1 - ci.j0, 0};
+            p.in = DirDesc{j1 - ci.j0, 0, 1, 0};
             if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.in.tiles);
-            launch_move(U, e->vec, wgs, e->s_in, p);
+            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_in, p, MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr});
             HIPTRY(e, hipGetLastError());
             n_ops++;
             ci.p0 = p1;
@@ -667,13 +682,14 @@ int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, con
         if (rc != KV_OK) return rc;
         int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
         if (path != KV_PATH_SDMA_STAGED) {
+            int32_t *po = dh, *pi = dh + 2 * (size_t)no;
             if (no) {
-                memcpy(dh, oi, (size_t)no * sizeof(int32_t));
-                memcpy(dh + no, os, (size_t)no * sizeof(int32_t));
+                memcpy(po, oi, (size_t)no * sizeof(int32_t));
+                memcpy(po + no, os, (size_t)no * sizeof(int32_t));
             }
             if (ni) {
-                memcpy(dh + 2 * (size_t)no, ii, (size_t)ni * sizeof(int32_t));
-                memcpy(dh + 2 * (size_t)no + ni, is, (size_t)ni * sizeof(int32_t));
+                memcpy(pi, ii, (size_t)ni * sizeof(int32_t));
+                memcpy(pi + ni, is, (size_t)ni * sizeof(int32_t));
             }
             rc = run_zero_copy(e, path, k, no, ni);
         } else {

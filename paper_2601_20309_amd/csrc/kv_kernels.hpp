@@ -18,14 +18,17 @@ namespace dkv {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kThreads = 256;  // 4 waves per workgroup
+constexpr int kThreads = 256;      // default lanes per workgroup (4 waves)
+constexpr int kMaxThreads = 1024;  // the move kernels take their tile width from blockDim.x, up to this
 
-// One direction's block list as the kernel sees it.
+// One direction's block list as the kernel sees it.  The id arrays themselves
+// are separate __restrict__ kernel arguments so that the compiler fetches them
+// with scalar loads (their own counter, off the vector-memory critical path).
 struct DirDesc {
-    const int32_t *ids;    // HBM block ids, device-readable
-    const int32_t *slots;  // far-side slots; nullptr = slot i is list index i
-    uint32_t n;            // blocks
-    uint32_t tiles;        // n * n_planes * tiles_per_seg
+    uint32_t n;      // blocks
+    uint32_t tiles;  // n * n_planes * tiles_per_seg
+    uint32_t iota;   // 1: far-side slot of list entry i is i itself (staging); 0: slots[i]
+    uint32_t pad;
 };
 
 // Addressing (Section 4.3.1 of the paper: layer x block x segment):
@@ -43,8 +46,9 @@ struct MoveParams {
     uint32_t plane0;         // first plane this launch covers
     uint32_t n_planes;       // planes this launch covers
     uint32_t vec_per_seg;    // seg_bytes / sizeof(V)
-    uint32_t tiles_per_seg;  // ceil(vec_per_seg / (kThreads * U))
+    uint32_t tiles_per_seg;  // ceil(vec_per_seg / (lanes per workgroup * U))
     uint32_t plane_major;    // tile order: 1 = [plane][i][tile], 0 = [i][plane][tile]
+    uint32_t full_tiles;     // 1: vec_per_seg is a multiple of the tile, no lane is ever out of range
     DirDesc out, in;
 };
 
@@ -63,11 +67,12 @@ __device__ __forceinline__ void st_hbm(V *p, V v)
     else *p = v;
 }
 
-// Tile t of direction d -> byte offsets of its segment and first vector index.
-__device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d, uint32_t t,
+// Tile t of direction d -> byte offsets (segment base + tile start) on both sides.
+__device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d,
+                                       const int32_t *__restrict__ ids,
+                                       const int32_t *__restrict__ slots, uint32_t t,
                                        uint64_t slot_stride, uint64_t plane_stride,
-                                       uint64_t &hbm_off, uint64_t &far_off, uint32_t &v0,
-                                       uint32_t tile_vecs)
+                                       uint32_t tile_bytes, uint64_t &hbm_off, uint64_t &far_off)
 {
     const uint32_t segidx = t / p.tiles_per_seg;
     const uint32_t tin = t - segidx * p.tiles_per_seg;
@@ -80,81 +85,180 @@ __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d, ui
         pl = segidx - i * p.n_planes;
     }
     pl += p.plane0;
-    const uint32_t id = (uint32_t)d.ids[i];
-    const uint32_t slot = d.slots ? (uint32_t)d.slots[i] : i;
-    hbm_off = (uint64_t)pl * p.hbm_plane_stride + (uint64_t)id * p.seg_bytes;
-    far_off = (uint64_t)slot * slot_stride + (uint64_t)pl * plane_stride;
-    v0 = tin * tile_vecs;
+    const uint32_t id = (uint32_t)ids[i];
+    const uint32_t slot = d.iota ? i : (uint32_t)slots[i];
+    hbm_off = (uint64_t)pl * p.hbm_plane_stride + (uint64_t)id * p.seg_bytes + (uint64_t)tin * tile_bytes;
+    far_off = (uint64_t)slot * slot_stride + (uint64_t)pl * plane_stride + (uint64_t)tin * tile_bytes;
+}
+
+// Everything one lane needs to move its share of one tile.  Which directions
+// take part is a compile-time property of the loop the tile belongs to, so the
+// hot loops are straight-line code and the compiler can count exactly how many
+// loads may stay in flight at each store.
+template <typename V>
+struct LaneTile {
+    const V *src_i;
+    V *dst_i;
+    const V *src_o;
+    V *dst_o;
+};
+
+template <typename V, bool IN, bool OUT>
+__device__ __forceinline__ LaneTile<V> lane_tile(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                                 const int32_t *__restrict__ out_slots,
+                                                 const int32_t *__restrict__ in_ids,
+                                                 const int32_t *__restrict__ in_slots, uint32_t t,
+                                                 uint32_t tile_vecs, uint32_t tid)
+{
+    LaneTile<V> r{nullptr, nullptr, nullptr, nullptr};
+    const uint32_t tile_bytes = tile_vecs * (uint32_t)sizeof(V);
+    if constexpr (IN) {
+        uint64_t ho, fo;
+        locate(p, p.in, in_ids, in_slots, t, p.far_slot_stride_in, p.far_plane_stride_in, tile_bytes, ho, fo);
+        r.src_i = reinterpret_cast<const V *>(p.far_in + fo) + tid;
+        r.dst_i = reinterpret_cast<V *>(p.hbm + ho) + tid;
+    }
+    if constexpr (OUT) {
+        uint64_t ho, fo;
+        locate(p, p.out, out_ids, out_slots, t, p.far_slot_stride_out, p.far_plane_stride_out, tile_bytes, ho, fo);
+        r.src_o = reinterpret_cast<const V *>(p.hbm + ho) + tid;
+        r.dst_o = reinterpret_cast<V *>(p.far_out + fo) + tid;
+    }
+    return r;
+}
+
+// Loads of one full tile: the far-side (host) loads first, they have the long
+// latency; then the HBM loads.  No lane predicate: all issue back to back.
+template <typename V, int U, bool NT, bool IN, bool OUT>
+__device__ __forceinline__ void tile_loads(const LaneTile<V> &a, uint32_t lanes, V (&vi)[U], V (&vo)[U])
+{
+    if constexpr (IN) {
+#pragma unroll
+        for (int u = 0; u < U; u++) vi[u] = a.src_i[u * lanes];
+    }
+    if constexpr (OUT) {
+#pragma unroll
+        for (int u = 0; u < U; u++) vo[u] = ld_hbm<NT>(a.src_o + u * lanes);
+    }
+}
+
+template <typename V, int U, bool NT, bool IN, bool OUT>
+__device__ __forceinline__ void tile_stores(const LaneTile<V> &a, uint32_t lanes, const V (&vi)[U], const V (&vo)[U])
+{
+    if constexpr (OUT) {
+#pragma unroll
+        for (int u = 0; u < U; u++) a.dst_o[u * lanes] = vo[u];
+    }
+    if constexpr (IN) {
+#pragma unroll
+        for (int u = 0; u < U; u++) st_hbm<NT>(a.dst_i + u * lanes, vi[u]);
+    }
+}
+
+// Tiles t, t + stride, ... below t_end, all full, all with the same directions.
+// Software pipelined in registers: the loads of the workgroup's next tile are
+// issued before the stores of the current one, so each lane keeps up to 2 * U
+// vectors per direction in flight and the link sees no gap between a
+// workgroup's tiles.  Returns the first tile index >= t_end of this workgroup.
+template <typename V, int U, bool NT, bool IN, bool OUT>
+__device__ __forceinline__ uint32_t run_full(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                             const int32_t *__restrict__ out_slots,
+                                             const int32_t *__restrict__ in_ids,
+                                             const int32_t *__restrict__ in_slots, uint32_t t, uint32_t t_end,
+                                             uint32_t stride, uint32_t lanes, uint32_t tid)
+{
+    if (t >= t_end) return t;
+    const uint32_t tile_vecs = lanes * U;
+    LaneTile<V> cur = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+    V ai[U], ao[U];
+    tile_loads<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+    for (t += stride; t < t_end; t += stride) {
+        const LaneTile<V> nxt = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+        V bi[U], bo[U];
+        tile_loads<V, U, NT, IN, OUT>(nxt, lanes, bi, bo);
+        tile_stores<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+        cur = nxt;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            if constexpr (IN) ai[u] = bi[u];
+            if constexpr (OUT) ao[u] = bo[u];
+        }
+    }
+    tile_stores<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+    return t;
+}
+
+// One tile with per-lane range checks: only for shapes whose segments are not
+// a whole number of tiles.
+template <typename V, int U, bool NT>
+__device__ __forceinline__ void tile_ragged(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                            const int32_t *__restrict__ out_slots,
+                                            const int32_t *__restrict__ in_ids,
+                                            const int32_t *__restrict__ in_slots, uint32_t t, uint32_t lanes,
+                                            uint32_t tid)
+{
+    const uint32_t tile_vecs = lanes * U;
+    const bool do_in = t < p.in.tiles, do_out = t < p.out.tiles;
+    const uint32_t v0 = (t % p.tiles_per_seg) * tile_vecs + tid;
+    V vi[U], vo[U];
+    if (do_in) {
+        const LaneTile<V> a = lane_tile<V, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (v0 + u * lanes < p.vec_per_seg) vi[u] = a.src_i[u * lanes];
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (v0 + u * lanes < p.vec_per_seg) st_hbm<NT>(a.dst_i + u * lanes, vi[u]);
+    }
+    if (do_out) {
+        const LaneTile<V> a = lane_tile<V, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (v0 + u * lanes < p.vec_per_seg) vo[u] = ld_hbm<NT>(a.src_o + u * lanes);
+#pragma unroll
+        for (int u = 0; u < U; u++)
+            if (v0 + u * lanes < p.vec_per_seg) a.dst_o[u * lanes] = vo[u];
+    }
 }
 
 // V: vector moved per lane (16 bytes when the segment allows it).
-// U: vectors per lane per tile; a tile is kThreads * U consecutive vectors of
+// U: vectors per lane per tile; a tile is blockDim.x * U consecutive vectors of
 //    one segment, so every wave touches 64 * sizeof(V) contiguous bytes per
 //    access on both sides (full 1 KiB rows at V = 16 bytes).
-// Workgroup g takes tiles g, g + G, ... of BOTH directions; a direction that
-// has run out of tiles is simply skipped, so the lists may differ in length or
-// be empty.
+// Workgroup g takes tiles g, g + G, ... .  Tile index t means tile t of the out
+// list and tile t of the in list: while both lists last, every lane alternates
+// an out-vector with an in-vector, which locks the two link directions 1:1;
+// the longer list's remainder then runs alone.  Lists may be empty.
 template <typename V, int U, bool NT>
-__global__ __launch_bounds__(kThreads) void kv_move_kernel(const MoveParams p)
+__global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p,
+                                                              const int32_t *__restrict__ out_ids,
+                                                              const int32_t *__restrict__ out_slots,
+                                                              const int32_t *__restrict__ in_ids,
+                                                              const int32_t *__restrict__ in_slots)
 {
-    const uint32_t tid = threadIdx.x;
-    const uint32_t tile_vecs = kThreads * U;
-    const uint32_t n_tiles = p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles;
-    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        const bool do_in = t < p.in.tiles;
-        const bool do_out = t < p.out.tiles;
-        V vi[U], vo[U];
-        const V *src_i = nullptr, *src_o = nullptr;
-        V *dst_i = nullptr, *dst_o = nullptr;
-        uint32_t v0_i = 0, v0_o = 0;
-        if (do_in) {
-            uint64_t ho, fo;
-            locate(p, p.in, t, p.far_slot_stride_in, p.far_plane_stride_in, ho, fo, v0_i, tile_vecs);
-            src_i = reinterpret_cast<const V *>(p.far_in + fo);
-            dst_i = reinterpret_cast<V *>(p.hbm + ho);
-        }
-        if (do_out) {
-            uint64_t ho, fo;
-            locate(p, p.out, t, p.far_slot_stride_out, p.far_plane_stride_out, ho, fo, v0_o, tile_vecs);
-            src_o = reinterpret_cast<const V *>(p.hbm + ho);
-            dst_o = reinterpret_cast<V *>(p.far_out + fo);
-        }
-        // far-side (host) loads first: they have the long latency
-        if (do_in) {
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const uint32_t v = v0_i + u * kThreads + tid;
-                if (v < p.vec_per_seg) vi[u] = src_i[v];
-            }
-        }
-        if (do_out) {
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const uint32_t v = v0_o + u * kThreads + tid;
-                if (v < p.vec_per_seg) vo[u] = ld_hbm<NT>(src_o + v);
-            }
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const uint32_t v = v0_o + u * kThreads + tid;
-                if (v < p.vec_per_seg) dst_o[v] = vo[u];
-            }
-        }
-        if (do_in) {
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const uint32_t v = v0_i + u * kThreads + tid;
-                if (v < p.vec_per_seg) st_hbm<NT>(dst_i + v, vi[u]);
-            }
-        }
+    const uint32_t tid = threadIdx.x, lanes = blockDim.x, stride = gridDim.x;
+    const uint32_t n_both = p.out.tiles < p.in.tiles ? p.out.tiles : p.in.tiles;
+    const uint32_t n_all = p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles;
+    uint32_t t = blockIdx.x;
+    if (!p.full_tiles) {
+        for (; t < n_all; t += stride) tile_ragged<V, U, NT>(p, out_ids, out_slots, in_ids, in_slots, t, lanes, tid);
+        return;
     }
+    t = run_full<V, U, NT, true, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_both, stride, lanes, tid);
+    if (p.out.tiles > p.in.tiles)
+        run_full<V, U, NT, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
+    else
+        run_full<V, U, NT, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
 }
 
 // Synthetic decode reader: streams every segment of the named blocks, plane by
 // plane (layer-major, as attention over the running requests would), and adds
 // up all 32-bit words modulo 2^64.  HBM-bound; read-only.  One tile is
-// kThreads * U 16-byte vectors of one segment; tiles are dealt round-robin so
-// neighbouring workgroups (which sit on different XCDs) stream neighbouring
-// 4 KiB * U pieces and every HBM channel stays busy.
+// kThreads * U 16-byte vectors of one segment; persistent workgroups take
+// tiles g, g + G, ..., so neighbouring workgroups (which sit on different
+// XCDs) stream neighbouring pieces and every HBM channel stays busy.
+// (One short-lived workgroup per few tiles, left to the hardware dispatcher,
+// measured 27 % slower.)
 struct ReadParams {
     const uint8_t *hbm;
     const int32_t *ids;

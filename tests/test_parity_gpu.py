@@ -189,3 +189,13 @@ def test_create_rejects_undersized_cache():
     assert ei.value.code == B.KV_EINVAL
     with pytest.raises(B.KVError):
         B.Engine(cfg, small.data_ptr(), host_pool_ptr=small.data_ptr())   # pool must be host memory
+
+
+@pytest.mark.parametrize("lanes", [64, 512, 1024])
+def test_workgroup_width(lanes):
+    """The move kernels take their tile width from the launch: any multiple of 64 lanes."""
+    for name, path in [("ragged", B.KV_PATH_FUSED), ("small8b", B.KV_PATH_FUSED), ("small8b", B.KV_PATH_ZEROCOPY)]:
+        case, rot = make_case(name, B.KV_HOST_BLOCK_FIRST, path, wg_lanes=lanes)
+        case.rotate(rot)
+        case.check()
+        case.close()
