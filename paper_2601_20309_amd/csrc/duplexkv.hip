@@ -163,7 +163,7 @@ struct kv_engine {
     hipStream_t s_read = nullptr;
     int32_t *read_ids = nullptr;               // device, n_hbm_blocks ints
     int32_t *read_ids_host = nullptr;          // pinned
-    unsigned long long *read_acc = nullptr;    // device
+    unsigned long long *read_acc = nullptr;    // device: [0] sum, then one 32-bit tile counter per pass
     unsigned long long *read_acc_host = nullptr;  // pinned
     std::vector<hipEvent_t> read_ev;           // passes + 1 timestamps
     int32_t read_passes = 0;
@@ -1017,7 +1017,7 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
         const size_t idb = (size_t)e->cfg.n_hbm_blocks * sizeof(int32_t);
         if (hipMalloc((void **)&e->read_ids, idb) != hipSuccess ||
             hipHostMalloc((void **)&e->read_ids_host, idb, hipHostMallocDefault) != hipSuccess ||
-            hipMalloc((void **)&e->read_acc, sizeof(unsigned long long)) != hipSuccess ||
+            hipMalloc((void **)&e->read_acc, sizeof(unsigned long long) + 256 * sizeof(unsigned int)) != hipSuccess ||
             hipHostMalloc((void **)&e->read_acc_host, sizeof(unsigned long long), hipHostMallocDefault) !=
                 hipSuccess) {
             (void)hipGetLastError();
@@ -1043,7 +1043,7 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
     p.tiles_per_seg = (p.vec_per_seg + dkv::kThreads * U - 1) / (dkv::kThreads * U);
     if (!dir_tiles(p.n, p.n_planes, p.tiles_per_seg, p.tiles)) return KV_EUNSUP;
     *e->read_acc_host = 0;
-    HIPTRY(e, hipMemsetAsync(e->read_acc, 0, sizeof(unsigned long long), e->s_read));
+    HIPTRY(e, hipMemsetAsync(e->read_acc, 0, sizeof(unsigned long long) + 256 * sizeof(unsigned int), e->s_read));
     if (n > 0) {
         memcpy(e->read_ids_host, ids, (size_t)n * sizeof(int32_t));
         HIPTRY(e, hipMemcpyAsync(e->read_ids, e->read_ids_host, (size_t)n * sizeof(int32_t),
@@ -1055,6 +1055,7 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
     HIPTRY(e, hipEventRecord(e->read_ev[0], e->s_read));
     for (int32_t k = 0; k < passes; k++) {
         if (p.tiles > 0) {
+            p.next = reinterpret_cast<unsigned int *>(e->read_acc + 1) + k;
             hipLaunchKernelGGL((dkv::kv_reader_kernel<U>), dim3((unsigned)wgs), dim3(dkv::kThreads), 0, e->s_read, p);
             HIPTRY(e, hipGetLastError());
         }

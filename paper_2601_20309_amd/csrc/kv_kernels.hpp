@@ -254,11 +254,12 @@ __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p
 // Synthetic decode reader: streams every segment of the named blocks, plane by
 // plane (layer-major, as attention over the running requests would), and adds
 // up all 32-bit words modulo 2^64.  HBM-bound; read-only.  One tile is
-// kThreads * U 16-byte vectors of one segment; persistent workgroups take
-// tiles g, g + G, ..., so neighbouring workgroups (which sit on different
-// XCDs) stream neighbouring pieces and every HBM channel stays busy.
-// (One short-lived workgroup per few tiles, left to the hardware dispatcher,
-// measured 27 % slower.)
+// kThreads * U 16-byte vectors of one segment.  Persistent workgroups claim
+// runs of kReadClaim tiles from a counter, in tile order, so at any moment the
+// chip streams one contiguous front of the cache, and a CU that is slowed by a
+// co-running kernel simply claims less (with a fixed share per workgroup the
+// slowest CU sets the pace of the whole pass).  One short-lived workgroup per
+// few tiles, left to the hardware dispatcher, measured 27 % slower.
 struct ReadParams {
     const uint8_t *hbm;
     const int32_t *ids;
@@ -270,14 +271,25 @@ struct ReadParams {
     uint32_t vec_per_seg;    // seg_bytes / 16
     uint32_t tiles_per_seg;
     uint32_t tiles;          // n * n_planes * tiles_per_seg
+    unsigned int *next;      // tile counter of this pass, zero at launch
 };
+
+constexpr uint32_t kReadClaim = 4;  // tiles a workgroup claims per turn
 
 template <int U>
 __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
 {
     const uint32_t tid = threadIdx.x;
     unsigned long long sum = 0;
-    for (uint32_t t = blockIdx.x; t < p.tiles; t += gridDim.x) {
+    __shared__ uint32_t claimed;
+    for (;;) {
+        if (tid == 0) claimed = atomicAdd(p.next, kReadClaim);
+        __syncthreads();
+        const uint32_t t0 = claimed;
+        __syncthreads();
+        if (t0 >= p.tiles) break;
+        const uint32_t t1 = min(p.tiles, t0 + kReadClaim);
+        for (uint32_t t = t0; t < t1; t++) {
         const uint32_t segidx = t / p.tiles_per_seg;
         const uint32_t tin = t - segidx * p.tiles_per_seg;
         const uint32_t pl = segidx / p.n;
@@ -294,6 +306,7 @@ __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
 #pragma unroll
         for (int u = 0; u < U; u++)
             sum += (unsigned long long)v[u].x + v[u].y + (unsigned long long)v[u].z + v[u].w;
+        }
     }
     // wave reduction, then one atomic per wave
 #pragma unroll

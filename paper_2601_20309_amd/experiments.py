@@ -3,6 +3,7 @@
   python -m paper_2601_20309_amd.experiments ladder        # analogue of the paper's Table 2
   python -m paper_2601_20309_amd.experiments configs       # configs[1..3] of the benchmark spec, default path
   python -m paper_2601_20309_amd.experiments interference  # configs[4]: rotation beside a decode reader
+  python -m paper_2601_20309_amd.experiments reader        # the decode reader alone (profiling target)
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -183,8 +184,9 @@ def interference():
     print("| rotation path | copy WGs | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
           "reader alone TB/s | reader beside rotation TB/s |")
     print("|---|---|---|---|---|---|")
-    for path, wgs, contiguous in [(B.KV_PATH_FUSED, 0, False), (B.KV_PATH_FUSED, 32, False),
-                                  (B.KV_PATH_FUSED, 16, False), (B.KV_PATH_SDMA_STAGED, 0, True)]:
+    for path, wgs, contiguous in [(B.KV_PATH_FUSED, 0, False), (B.KV_PATH_FUSED, 48, False),
+                                  (B.KV_PATH_FUSED, 32, False), (B.KV_PATH_FUSED, 16, False),
+                                  (B.KV_PATH_SDMA_STAGED, 0, True)]:
         rot = W.config_rotation(name, contiguous_slots=contiguous)
         named = np.zeros(shape.n_hbm_blocks, bool)
         named[rot.out_ids] = True; named[rot.in_ids] = True
@@ -216,19 +218,43 @@ def interference():
             assert rc == 0
             if i >= 1:
                 both.append(dt)
-                # passes that ran entirely inside the rotation window
+                # passes that ran entirely inside the rotation window: bytes read / their time
                 acc, inside = 0.0, []
                 for p in pm2:
                     if acc + p <= dt:
                         inside.append(p)
                     acc += p
-                read_both.append(read_bytes / statistics.median(inside[1:] or pm2) / 1e9)
+                inside = inside[1:] or pm2      # the first one started before the rotation
+                read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
         ms_both = statistics.median(both)
         print(f"| {B.PATH_NAMES[path]} | {wgs or 'default'} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
               f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
         eng.kv_destroy()
 
 
+def reader():
+    """The decode reader alone (for profiling): 8 passes over 19200 blocks, plus a
+    plain 256 MiB device copy as the known-size reference for the counters."""
+    shape = W.SHAPES["interference"]
+    cache = _cache(shape)
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    ids = np.arange(19200, dtype=np.int32)
+    a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    assert eng.kv_reader_start(ids, 8) == 0
+    rc, _, pm = eng.kv_reader_wait()
+    assert rc == 0
+    ms = statistics.median(pm[1:])
+    nbytes = len(ids) * blk
+    print(f"kv_reader_kernel: {nbytes / 2**30:.2f} GiB per pass, median pass {ms:.3f} ms = {nbytes / ms / 1e9:.3f} TB/s "
+          f"= {100 * nbytes / ms / 1e9 / 8.0:.1f} % of the 8 TB/s HBM peak")
+    eng.kv_destroy()
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "configs"
-    {"ladder": ladder, "configs": configs, "interference": interference}[what]()
+    {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader}[what]()
