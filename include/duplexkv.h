@@ -165,7 +165,8 @@ int kv_last_stats(kv_engine *engine, kv_stats *out);
  * the current device: the denominator the rotation is judged against, measured
  * the way Appendix B measures its link (copy-engine memcpy, one direction and
  * both at once, median of `reps`).  Outputs in GB/s (1e9 bytes per second);
- * the *_duplex figures are per direction while both run.
+ * the *_duplex figures are per direction while both run, best of several
+ * stream pairings (streams share a few hardware queues).
  */
 int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d,
                   double *d2h_duplex, double *h2d_duplex);

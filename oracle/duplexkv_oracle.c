@@ -305,3 +305,291 @@ int okv_rotate_threads(const okv_shape *s, uint8_t *hbm, uint8_t *pool,
     free(sh);
     return OKV_OK;
 }
+
+/* ------------------------------------------------------------------------
+ * Block table with eager block rotation (paper Section 4.3.2, "Eager block
+ * rotation for data race free overlapping"), as a plain state machine.
+ *
+ * A request's KV grows token by token; a block that is still being filled is
+ * DIRTY, a filled block is FULL until its copy to DRAM has been issued and
+ * SYNCED afterwards (valid copies in HBM and in DRAM), and the blocks of a
+ * preempted request are HOST (DRAM only).  The eager step copies FULL blocks
+ * out in the background; at preemption only blocks without a valid DRAM copy
+ * (the dirty tail, and any FULL block the eager step has not reached) are
+ * copied, the HBM blocks of SYNCED ones are released at once without moving
+ * a byte; a resumed request is copied back whole and keeps its DRAM copies,
+ * so it is SYNCED again.  Blocks released by SYNCED drops may be reused by
+ * the swap-ins of the same rotation; blocks that the same rotation copies out
+ * may not (that is the race the section describes).
+ *
+ * Readings where the paper is silent: allocation takes the lowest-numbered
+ * free HBM block / host slot; the eager step visits requests by ascending id
+ * and blocks by ascending index; a request keeps its host slots until it
+ * finishes; appending to a partly filled block makes it DIRTY again.
+ * Everything is linear scans over small arrays: slow and easy to check.
+ * ------------------------------------------------------------------------ */
+enum { OKV_ENOSPC = -8 };
+enum { OKVT_NONE = 0, OKVT_DIRTY = 1, OKVT_FULL = 2, OKVT_SYNCED = 3, OKVT_HOST = 4 };
+
+typedef struct {
+    int32_t used;      /* request exists */
+    int32_t resident;  /* 1 running (in HBM), 0 rotary (in DRAM) */
+    int32_t len;       /* tokens */
+    int32_t n;         /* blocks */
+    int32_t *hbm, *slot, *state;
+} okvt_req;
+
+typedef struct okvt {
+    okv_shape s;
+    int32_t max_req;
+    okvt_req *req;
+    int32_t *hbm_owner;  /* -1 free, else request id */
+    int32_t *slot_owner;
+    int64_t copied_eager, copied_preempt, dropped_synced, swapped_in;
+} okvt;
+
+okvt *okvt_create(const okv_shape *s, int32_t max_requests)
+{
+    if (!shape_ok(s) || max_requests <= 0)
+        return NULL;
+    okvt *t = (okvt *)calloc(1, sizeof(okvt));
+    t->s = *s;
+    t->max_req = max_requests;
+    t->req = (okvt_req *)calloc((size_t)max_requests, sizeof(okvt_req));
+    t->hbm_owner = (int32_t *)malloc(sizeof(int32_t) * (size_t)s->n_hbm_blocks);
+    t->slot_owner = (int32_t *)malloc(sizeof(int32_t) * (size_t)s->n_host_slots);
+    for (int32_t i = 0; i < s->n_hbm_blocks; i++) t->hbm_owner[i] = -1;
+    for (int32_t i = 0; i < s->n_host_slots; i++) t->slot_owner[i] = -1;
+    return t;
+}
+
+void okvt_destroy(okvt *t)
+{
+    if (!t) return;
+    for (int32_t r = 0; r < t->max_req; r++) {
+        free(t->req[r].hbm);
+        free(t->req[r].slot);
+        free(t->req[r].state);
+    }
+    free(t->req);
+    free(t->hbm_owner);
+    free(t->slot_owner);
+    free(t);
+}
+
+static int32_t count_free(const int32_t *owner, int32_t n)
+{
+    int32_t c = 0;
+    for (int32_t i = 0; i < n; i++) c += owner[i] < 0;
+    return c;
+}
+
+static int32_t lowest_free(const int32_t *owner, int32_t n)
+{
+    for (int32_t i = 0; i < n; i++)
+        if (owner[i] < 0) return i;
+    return -1;
+}
+
+static int32_t blocks_for(const okvt *t, int32_t tokens)
+{
+    return (tokens + t->s.block_size - 1) / t->s.block_size;
+}
+
+/* Grow request `req` by n_tokens (creating it if it does not exist).  Reports
+ * the HBM ids of blocks newly allocated for it.  All-or-nothing. */
+int okvt_append(okvt *t, int32_t req, int32_t n_tokens, int32_t *new_ids, int32_t cap, int32_t *n_new)
+{
+    if (!t || req < 0 || req >= t->max_req || n_tokens < 0) return OKV_EINVAL;
+    okvt_req *r = &t->req[req];
+    if (r->used && !r->resident) return OKV_EINVAL; /* a rotary request cannot generate */
+    int32_t old_n = r->used ? r->n : 0, old_len = r->used ? r->len : 0;
+    int32_t need = blocks_for(t, old_len + n_tokens) - old_n;
+    if (need > count_free(t->hbm_owner, t->s.n_hbm_blocks)) return OKV_ENOSPC;
+    if (new_ids && need > cap) return OKV_EINVAL;
+    if (!r->used) {
+        r->used = 1;
+        r->resident = 1;
+        r->len = 0;
+        r->n = 0;
+        if (!r->hbm) {
+            r->hbm = (int32_t *)malloc(sizeof(int32_t) * (size_t)t->s.n_hbm_blocks);
+            r->slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)t->s.n_hbm_blocks);
+            r->state = (int32_t *)malloc(sizeof(int32_t) * (size_t)t->s.n_hbm_blocks);
+        }
+    }
+    /* tokens that land in the current tail block make it dirty again */
+    if (n_tokens > 0 && old_len % t->s.block_size != 0) r->state[old_n - 1] = OKVT_DIRTY;
+    for (int32_t k = 0; k < need; k++) {
+        int32_t b = lowest_free(t->hbm_owner, t->s.n_hbm_blocks);
+        t->hbm_owner[b] = req;
+        r->hbm[r->n] = b;
+        r->slot[r->n] = -1;
+        r->state[r->n] = OKVT_DIRTY;
+        if (new_ids) new_ids[k] = b;
+        r->n++;
+    }
+    r->len = old_len + n_tokens;
+    /* every block that is now completely filled and was being filled is FULL */
+    for (int32_t i = 0; i < r->n; i++) {
+        int32_t filled = (i + 1) * t->s.block_size <= r->len;
+        if (filled && r->state[i] == OKVT_DIRTY) r->state[i] = OKVT_FULL;
+    }
+    if (n_new) *n_new = need;
+    return OKV_OK;
+}
+
+/* Background step: copy up to `budget` FULL blocks of running requests to DRAM. */
+int okvt_eager(okvt *t, uint8_t *hbm, uint8_t *pool, int32_t budget, int32_t *n_done)
+{
+    if (!t || budget < 0) return OKV_EINVAL;
+    int32_t done = 0;
+    for (int32_t q = 0; q < t->max_req && done < budget; q++) {
+        okvt_req *r = &t->req[q];
+        if (!r->used || !r->resident) continue;
+        for (int32_t i = 0; i < r->n && done < budget; i++) {
+            if (r->state[i] != OKVT_FULL) continue;
+            if (r->slot[i] < 0) {
+                int32_t sl = lowest_free(t->slot_owner, t->s.n_host_slots);
+                if (sl < 0) goto out; /* pool exhausted: sync what fits */
+                t->slot_owner[sl] = q;
+                r->slot[i] = sl;
+            }
+            block_out(&t->s, hbm, pool, r->hbm[i], r->slot[i]);
+            r->state[i] = OKVT_SYNCED;
+            done++;
+        }
+    }
+out:
+    t->copied_eager += done;
+    if (n_done) *n_done = done;
+    return OKV_OK;
+}
+
+static int in_list(const int32_t *p, int32_t n, int32_t v)
+{
+    for (int32_t i = 0; i < n; i++)
+        if (p[i] == v) return 1;
+    return 0;
+}
+
+/* One rotation: `pre` requests leave HBM, `res` requests come back. */
+int okvt_rotate(okvt *t, uint8_t *hbm, uint8_t *pool, const int32_t *pre, int32_t n_pre,
+                const int32_t *res, int32_t n_res)
+{
+    if (!t || list_bad(pre, n_pre) || list_bad(res, n_res)) return OKV_EINVAL;
+    for (int32_t i = 0; i < n_pre; i++) {
+        if (pre[i] < 0 || pre[i] >= t->max_req) return OKV_EINVAL;
+        okvt_req *r = &t->req[pre[i]];
+        if (!r->used || !r->resident || in_list(pre, i, pre[i])) return OKV_EINVAL;
+    }
+    for (int32_t i = 0; i < n_res; i++) {
+        if (res[i] < 0 || res[i] >= t->max_req) return OKV_EINVAL;
+        okvt_req *r = &t->req[res[i]];
+        if (!r->used || r->resident || in_list(res, i, res[i])) return OKV_EINVAL;
+    }
+    /* room check before anything changes */
+    int32_t need_slots = 0, drop = 0, need_hbm = 0;
+    for (int32_t i = 0; i < n_pre; i++) {
+        okvt_req *r = &t->req[pre[i]];
+        for (int32_t b = 0; b < r->n; b++) {
+            if (r->state[b] == OKVT_SYNCED) drop++;
+            else if (r->slot[b] < 0) need_slots++;
+        }
+    }
+    for (int32_t i = 0; i < n_res; i++) need_hbm += t->req[res[i]].n;
+    if (need_slots > count_free(t->slot_owner, t->s.n_host_slots)) return OKV_ENOSPC;
+    if (need_hbm > count_free(t->hbm_owner, t->s.n_hbm_blocks) + drop) return OKV_ENOSPC;
+
+    /* 1. preempted requests: blocks without a valid DRAM copy are copied out;
+     *    SYNCED blocks give their HBM block back at once */
+    int32_t n_out = 0;
+    int32_t *held = (int32_t *)malloc(sizeof(int32_t) * (size_t)t->s.n_hbm_blocks);
+    for (int32_t i = 0; i < n_pre; i++) {
+        okvt_req *r = &t->req[pre[i]];
+        for (int32_t b = 0; b < r->n; b++) {
+            if (r->state[b] == OKVT_SYNCED) {
+                t->hbm_owner[r->hbm[b]] = -1;
+                t->dropped_synced++;
+            } else {
+                if (r->slot[b] < 0) {
+                    int32_t sl = lowest_free(t->slot_owner, t->s.n_host_slots);
+                    t->slot_owner[sl] = pre[i];
+                    r->slot[b] = sl;
+                }
+                block_out(&t->s, hbm, pool, r->hbm[b], r->slot[b]);
+                held[n_out++] = r->hbm[b]; /* stays unavailable during this rotation */
+                t->copied_preempt++;
+            }
+            r->hbm[b] = -1;
+            r->state[b] = OKVT_HOST;
+        }
+        r->resident = 0;
+    }
+    /* 2. resumed requests: every block comes back into the lowest free HBM block */
+    for (int32_t i = 0; i < n_res; i++) {
+        okvt_req *r = &t->req[res[i]];
+        for (int32_t b = 0; b < r->n; b++) {
+            int32_t id = lowest_free(t->hbm_owner, t->s.n_hbm_blocks);
+            t->hbm_owner[id] = res[i];
+            r->hbm[b] = id;
+            block_in(&t->s, hbm, pool, id, r->slot[b]);
+            r->state[b] = OKVT_SYNCED;
+            t->swapped_in++;
+        }
+        r->resident = 1;
+    }
+    /* 3. the copied-out blocks are free from now on */
+    for (int32_t k = 0; k < n_out; k++) t->hbm_owner[held[k]] = -1;
+    free(held);
+    return OKV_OK;
+}
+
+/* The request is done: its HBM blocks and host slots are free again. */
+int okvt_finish(okvt *t, int32_t req)
+{
+    if (!t || req < 0 || req >= t->max_req || !t->req[req].used) return OKV_EINVAL;
+    okvt_req *r = &t->req[req];
+    for (int32_t b = 0; b < r->n; b++) {
+        if (r->hbm[b] >= 0) t->hbm_owner[r->hbm[b]] = -1;
+        if (r->slot[b] >= 0) t->slot_owner[r->slot[b]] = -1;
+    }
+    r->used = 0;
+    r->n = 0;
+    r->len = 0;
+    return OKV_OK;
+}
+
+/* Mapping and state of a request's blocks; info = {len_tokens, resident}. */
+int okvt_blocks(const okvt *t, int32_t req, int32_t *ids, int32_t *slots, int32_t *states, int32_t cap,
+                int32_t *n, int32_t *info)
+{
+    if (!t || req < 0 || req >= t->max_req || !t->req[req].used || !n) return OKV_EINVAL;
+    const okvt_req *r = &t->req[req];
+    if (r->n > cap) return OKV_EINVAL;
+    for (int32_t b = 0; b < r->n; b++) {
+        if (ids) ids[b] = r->hbm[b];
+        if (slots) slots[b] = r->slot[b];
+        if (states) states[b] = r->state[b];
+    }
+    *n = r->n;
+    if (info) {
+        info[0] = r->len;
+        info[1] = r->resident;
+    }
+    return OKV_OK;
+}
+
+/* counts = {free HBM blocks, free host slots, blocks copied by the eager step,
+ * blocks copied at preemption, SYNCED blocks dropped without a copy, blocks swapped in} */
+int okvt_counts(const okvt *t, int64_t *counts)
+{
+    if (!t || !counts) return OKV_EINVAL;
+    counts[0] = count_free(t->hbm_owner, t->s.n_hbm_blocks);
+    counts[1] = count_free(t->slot_owner, t->s.n_host_slots);
+    counts[2] = t->copied_eager;
+    counts[3] = t->copied_preempt;
+    counts[4] = t->dropped_synced;
+    counts[5] = t->swapped_in;
+    return OKV_OK;
+}

@@ -19,7 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "duplexkv_oracle.c")
 _LIB = os.path.join(_HERE, "libduplexkv_oracle.so")
 
-OK, EINVAL, ERANGE, EDUP, EOVERLAP = 0, -1, -2, -3, -4
+OK, EINVAL, ERANGE, EDUP, EOVERLAP, ENOSPC = 0, -1, -2, -3, -4, -8
+NONE, DIRTY, FULL, SYNCED, HOST = 0, 1, 2, 3, 4   # block states of the table
 BLOCK_FIRST, LAYER_FIRST = 0, 1
 
 
@@ -64,6 +65,22 @@ def lib() -> C.CDLL:
         L.okv_swap_out.argtypes = [ps, C.c_void_p, C.c_void_p, p32, p32, C.c_int32]
         L.okv_swap_in.restype = C.c_int
         L.okv_swap_in.argtypes = [ps, C.c_void_p, C.c_void_p, p32, p32, C.c_int32]
+        L.okvt_create.restype = C.c_void_p
+        L.okvt_create.argtypes = [ps, C.c_int32]
+        L.okvt_destroy.restype = None
+        L.okvt_destroy.argtypes = [C.c_void_p]
+        L.okvt_append.restype = C.c_int
+        L.okvt_append.argtypes = [C.c_void_p, C.c_int32, C.c_int32, p32, C.c_int32, p32]
+        L.okvt_eager.restype = C.c_int
+        L.okvt_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, p32]
+        L.okvt_rotate.restype = C.c_int
+        L.okvt_rotate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, p32, C.c_int32, p32, C.c_int32]
+        L.okvt_finish.restype = C.c_int
+        L.okvt_finish.argtypes = [C.c_void_p, C.c_int32]
+        L.okvt_blocks.restype = C.c_int
+        L.okvt_blocks.argtypes = [C.c_void_p, C.c_int32, p32, p32, p32, C.c_int32, p32, p32]
+        L.okvt_counts.restype = C.c_int
+        L.okvt_counts.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
         L.okv_read_checksum.restype = C.c_int
         L.okv_read_checksum.argtypes = [ps, C.c_void_p, p32, C.c_int32, C.POINTER(C.c_uint64)]
         _lib = L
@@ -149,3 +166,61 @@ def read_checksum(s, hbm, ids):
     out = C.c_uint64(0)
     rc = lib().okv_read_checksum(C.byref(s), _buf(hbm), pi, n, C.byref(out))
     return rc, int(out.value)
+
+
+COUNT_NAMES = ("free_hbm", "free_slots", "copied_eager", "copied_preempt", "dropped_synced", "swapped_in")
+
+
+class Table:
+    """The oracle's block table with eager rotation, over caller-held images."""
+
+    def __init__(self, s, max_requests):
+        self.s = s
+        self._h = lib().okvt_create(C.byref(s), max_requests)
+        assert self._h
+
+    def append(self, req, n_tokens):
+        """(code, [newly allocated HBM ids])."""
+        cap = int(self.s.n_hbm_blocks)
+        ids = (C.c_int32 * cap)()
+        n = C.c_int32(0)
+        rc = lib().okvt_append(self._h, req, n_tokens, ids, cap, C.byref(n))
+        return rc, [ids[i] for i in range(n.value)] if rc == OK else []
+
+    def eager(self, hbm, pool, budget):
+        n = C.c_int32(0)
+        rc = lib().okvt_eager(self._h, _buf(hbm), _buf(pool), budget, C.byref(n))
+        return rc, n.value
+
+    def rotate(self, hbm, pool, preempt, resume):
+        pp, np_, k1 = _ids(preempt)
+        pr, nr, k2 = _ids(resume)
+        return lib().okvt_rotate(self._h, _buf(hbm), _buf(pool), pp, np_, pr, nr)
+
+    def finish(self, req):
+        return lib().okvt_finish(self._h, req)
+
+    def blocks(self, req):
+        """None if the request does not exist, else dict(ids, slots, states, len, resident)."""
+        cap = int(self.s.n_hbm_blocks)
+        ids, slots, states = (C.c_int32 * cap)(), (C.c_int32 * cap)(), (C.c_int32 * cap)()
+        n, info = C.c_int32(0), (C.c_int32 * 2)()
+        rc = lib().okvt_blocks(self._h, req, ids, slots, states, cap, C.byref(n), info)
+        if rc != OK:
+            return None
+        k = n.value
+        return dict(ids=list(ids[:k]), slots=list(slots[:k]), states=list(states[:k]), len=info[0],
+                    resident=bool(info[1]))
+
+    def counts(self):
+        c = (C.c_int64 * 8)()
+        assert lib().okvt_counts(self._h, c) == OK
+        return dict(zip(COUNT_NAMES, c[:6]))
+
+    def close(self):
+        if self._h:
+            lib().okvt_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()

@@ -943,11 +943,12 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double
     kv_engine *e = nullptr;  // HIPTRY wants one; no engine state here
     void *ha = nullptr, *hb = nullptr, *da = nullptr, *db = nullptr;
     // Streams share a few hardware queues and DMA engines; which pair a process
-    // gets depends on what else it has created.  Three streams give three
-    // pairings and the best one is reported: the link's ceiling, not a
-    // property of one unlucky pairing.
-    constexpr int kS = 3;
-    hipStream_t st[kS] = {nullptr, nullptr, nullptr};
+    // gets depends on what else it has created.  Five streams are more than
+    // the process has hardware queues; every pairing with stream 0 and 1 is
+    // timed and the best one is reported: the link's ceiling, not a property
+    // of one unlucky pairing.
+    constexpr int kS = 5;
+    hipStream_t st[kS] = {nullptr, nullptr, nullptr, nullptr, nullptr};
     auto cleanup = [&]() {
         if (ha) (void)hipHostFree(ha);
         if (hb) (void)hipHostFree(hb);
@@ -990,7 +991,7 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double
         if (pass(nullptr, st[1], ms) != KV_OK) return KV_EHIP;
         *h2d = bytes / ms / 1e6;
         best = 1e30;
-        const int pairs[3][2] = {{0, 1}, {0, 2}, {1, 2}};
+        const int pairs[7][2] = {{0, 1}, {0, 2}, {0, 3}, {0, 4}, {1, 2}, {1, 3}, {1, 4}};
         for (auto &pr : pairs) {
             if (pass(st[pr[0]], st[pr[1]], ms) != KV_OK) return KV_EHIP;
             best = std::min(best, ms);
