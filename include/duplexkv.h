@@ -45,6 +45,7 @@ extern "C" {
 #define KV_ENOMEM   (-5)  /* a device or pinned-host allocation failed */
 #define KV_EHIP     (-6)  /* HIP runtime failure (no device, launch or copy error); sticky */
 #define KV_EUNSUP   (-7)  /* the chosen path cannot serve this shape or request */
+#define KV_ENOSPC   (-8)  /* block table: not enough free HBM blocks or host slots */
 
 /* ---- host pool layouts ---- */
 #define KV_HOST_BLOCK_FIRST 0
@@ -189,6 +190,84 @@ int kv_reader_start(kv_engine *engine, const int32_t *block_ids, int32_t n, int3
  * or an array of `passes` doubles, device time of each pass (HIP events).
  */
 int kv_reader_wait(kv_engine *engine, uint64_t *checksum, double *ms_per_pass);
+
+/* ------------------------------------------------------------------------
+ * Block table with eager block rotation (Section 4.3.2, "Eager block rotation
+ * for data race free overlapping").  The table owns the allocation of the
+ * engine's HBM blocks and host slots and tracks, per block of every request,
+ * state and residency:
+ *   KV_BLOCK_DIRTY   still being filled; HBM only
+ *   KV_BLOCK_FULL    filled, copy to DRAM not yet issued; HBM only
+ *   KV_BLOCK_SYNCED  valid copies in HBM and in DRAM
+ *   KV_BLOCK_HOST    DRAM only (request preempted)
+ * Allocation always takes the lowest-numbered free block / slot.  A request
+ * keeps its host slots until kv_table_finish().  All calls only enqueue
+ * transfers on the engine's streams; kv_wait() on the engine completes them.
+ * Transfers the table issues are ordered so that a block or slot is never
+ * overwritten while an earlier transfer still reads it.  While a table exists
+ * the engine's kv_swap_out / kv_swap_in / kv_rotate must not be called.
+ * Request ids are 0 .. max_requests-1.
+ * ------------------------------------------------------------------------ */
+#define KV_BLOCK_DIRTY  1
+#define KV_BLOCK_FULL   2
+#define KV_BLOCK_SYNCED 3
+#define KV_BLOCK_HOST   4
+
+typedef struct kv_table kv_table; /* opaque, owned by the library */
+
+typedef struct {
+    int64_t free_hbm_blocks, free_host_slots;
+    int64_t copied_eager;    /* blocks copied out by kv_table_eager */
+    int64_t copied_preempt;  /* blocks copied out at preemption (no valid DRAM copy yet) */
+    int64_t dropped_synced;  /* HBM blocks released at preemption without moving a byte */
+    int64_t swapped_in;      /* blocks copied back at resumption */
+} kv_table_counts;
+
+int kv_table_create(kv_table **table, kv_engine *engine, int32_t max_requests);
+int kv_table_destroy(kv_table *table);
+
+/*
+ * Request `req` grows by n_tokens (it is created if new, and must be resident).
+ * HBM blocks are allocated as needed; new_block_ids (NULL, or room for `cap`
+ * ids) receives them and *n_new their count.  The caller then writes the new
+ * tokens' KV into the request's blocks.  Tokens that land in a partly filled
+ * block make it DIRTY; a block that fills up becomes FULL.  KV_ENOSPC, with
+ * nothing changed, if the cache has too few free blocks.
+ */
+int kv_table_append(kv_table *table, int32_t req, int32_t n_tokens, int32_t *new_block_ids, int32_t cap,
+                    int32_t *n_new);
+
+/*
+ * Eager rotation step: enqueue the copy to DRAM of up to `budget` FULL blocks
+ * of resident requests (ascending request id, then block index); they become
+ * SYNCED.  Stops early when the pool is exhausted.  *n_done = blocks issued.
+ */
+int kv_table_eager(kv_table *table, int32_t budget, int32_t *n_done);
+
+/*
+ * One rotation: the `preempt` requests leave HBM, the `resume` requests come
+ * back, as one duplex transfer.  Of a preempted request only blocks without a
+ * valid DRAM copy are copied (the dirty tail, FULL blocks the eager step has
+ * not reached); its SYNCED blocks are released at once and may be reused by
+ * this very call's swap-ins, while the blocks being copied out may not (the
+ * data race of Section 4.3.2).  A resumed request is copied back whole and is
+ * SYNCED.  KV_EINVAL for unknown / duplicated / wrongly placed requests,
+ * KV_ENOSPC if slots or blocks do not suffice; nothing changes on error.
+ */
+int kv_table_rotate(kv_table *table, const int32_t *preempt, int32_t n_preempt, const int32_t *resume,
+                    int32_t n_resume);
+
+/* The request is done: its HBM blocks and host slots are free again (the
+ * caller makes sure no transfer of them is still in flight). */
+int kv_table_finish(kv_table *table, int32_t req);
+
+/* Mapping of a request: per block HBM id (-1 if none), host slot (-1 if
+ * none), state; arrays may be NULL, else hold `cap` entries.  info[0] =
+ * tokens, info[1] = 1 if resident. */
+int kv_table_blocks(kv_table *table, int32_t req, int32_t *block_ids, int32_t *host_slots, int32_t *states,
+                    int32_t cap, int32_t *n, int32_t *info);
+
+int kv_table_get_counts(kv_table *table, kv_table_counts *out);
 
 const char *kv_strerror(int code);
 

@@ -16,8 +16,9 @@ import torch  # noqa: F401
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduplexkv.so")
 
-KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP = \
-    0, -1, -2, -3, -4, -5, -6, -7
+KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP, KV_ENOSPC = \
+    0, -1, -2, -3, -4, -5, -6, -7, -8
+KV_BLOCK_DIRTY, KV_BLOCK_FULL, KV_BLOCK_SYNCED, KV_BLOCK_HOST = 1, 2, 3, 4
 KV_HOST_BLOCK_FIRST, KV_HOST_LAYER_FIRST = 0, 1
 KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSED = 0, 1, 2, 3, 4
 PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"}
@@ -25,7 +26,8 @@ PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
            "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
            "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
-           "kv_strerror"]
+           "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate",
+           "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_strerror"]
 
 
 class kv_config(C.Structure):
@@ -39,6 +41,11 @@ class kv_stats(C.Structure):
     _fields_ = [("bytes_out", C.c_uint64), ("bytes_in", C.c_uint64), ("ms_out", C.c_double),
                 ("ms_in", C.c_double), ("ms_e2e", C.c_double), ("path_used", C.c_int32),
                 ("n_launches", C.c_int32)]
+
+
+class kv_table_counts(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("free_hbm_blocks", "free_host_slots", "copied_eager",
+                                         "copied_preempt", "dropped_synced", "swapped_in")]
 
 
 class KVError(RuntimeError):
@@ -81,6 +88,22 @@ def _load() -> C.CDLL:
     L.kv_reader_start.argtypes = [C.c_void_p, p32, C.c_int32, C.c_int32, C.c_int32]
     L.kv_reader_wait.restype = C.c_int
     L.kv_reader_wait.argtypes = [C.c_void_p, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]
+    L.kv_table_create.restype = C.c_int
+    L.kv_table_create.argtypes = [C.POINTER(C.c_void_p), C.c_void_p, C.c_int32]
+    L.kv_table_destroy.restype = C.c_int
+    L.kv_table_destroy.argtypes = [C.c_void_p]
+    L.kv_table_append.restype = C.c_int
+    L.kv_table_append.argtypes = [C.c_void_p, C.c_int32, C.c_int32, p32, C.c_int32, p32]
+    L.kv_table_eager.restype = C.c_int
+    L.kv_table_eager.argtypes = [C.c_void_p, C.c_int32, p32]
+    L.kv_table_rotate.restype = C.c_int
+    L.kv_table_rotate.argtypes = [C.c_void_p, p32, C.c_int32, p32, C.c_int32]
+    L.kv_table_finish.restype = C.c_int
+    L.kv_table_finish.argtypes = [C.c_void_p, C.c_int32]
+    L.kv_table_blocks.restype = C.c_int
+    L.kv_table_blocks.argtypes = [C.c_void_p, C.c_int32, p32, p32, p32, C.c_int32, p32, p32]
+    L.kv_table_get_counts.restype = C.c_int
+    L.kv_table_get_counts.argtypes = [C.c_void_p, C.POINTER(kv_table_counts)]
     L.kv_strerror.restype = C.c_char_p
     L.kv_strerror.argtypes = [C.c_int]
     return L
@@ -222,5 +245,69 @@ class Engine:
     def __del__(self):
         try:
             self.kv_destroy()
+        except Exception:
+            pass
+
+
+class Table:
+    """Owns one kv_table handle on top of an Engine (same names as the C ABI)."""
+
+    def __init__(self, engine: Engine, max_requests: int):
+        self.engine = engine
+        self._cap = int(engine.cfg.n_hbm_blocks)
+        self._h = C.c_void_p()
+        rc = lib.kv_table_create(C.byref(self._h), engine._h, max_requests)
+        if rc != KV_OK:
+            self._h = C.c_void_p()
+            raise KVError(rc, "kv_table_create")
+
+    def kv_table_append(self, req: int, n_tokens: int):
+        """(code, [newly allocated HBM block ids])."""
+        ids = (C.c_int32 * self._cap)()
+        n = C.c_int32(0)
+        rc = lib.kv_table_append(self._h, req, n_tokens, ids, self._cap, C.byref(n))
+        return rc, [ids[i] for i in range(n.value)] if rc == KV_OK else []
+
+    def kv_table_eager(self, budget: int):
+        n = C.c_int32(0)
+        rc = lib.kv_table_eager(self._h, budget, C.byref(n))
+        return rc, n.value
+
+    def kv_table_rotate(self, preempt, resume) -> int:
+        pp, np_, k1 = _ids(preempt)
+        pr, nr, k2 = _ids(resume)
+        return lib.kv_table_rotate(self._h, pp, np_, pr, nr)
+
+    def kv_table_finish(self, req: int) -> int:
+        return lib.kv_table_finish(self._h, req)
+
+    def kv_table_blocks(self, req: int):
+        """None if the request does not exist, else dict(ids, slots, states, len, resident)."""
+        ids, slots, states = ((C.c_int32 * self._cap)() for _ in range(3))
+        n, info = C.c_int32(0), (C.c_int32 * 2)()
+        rc = lib.kv_table_blocks(self._h, req, ids, slots, states, self._cap, C.byref(n), info)
+        if rc != KV_OK:
+            return None
+        k = n.value
+        return dict(ids=list(ids[:k]), slots=list(slots[:k]), states=list(states[:k]), len=info[0],
+                    resident=bool(info[1]))
+
+    def kv_table_get_counts(self) -> dict:
+        c = kv_table_counts()
+        rc = lib.kv_table_get_counts(self._h, C.byref(c))
+        if rc != KV_OK:
+            raise KVError(rc, "kv_table_get_counts")
+        return {f: getattr(c, f) for f, _ in kv_table_counts._fields_}
+
+    def kv_table_destroy(self) -> int:
+        if self._h:
+            rc = lib.kv_table_destroy(self._h)
+            self._h = C.c_void_p()
+            return rc
+        return KV_OK
+
+    def __del__(self):
+        try:
+            self.kv_table_destroy()
         except Exception:
             pass

@@ -29,11 +29,14 @@ def test_codes_match_header_and_oracle():
     text = open(os.path.join(ROOT, "include", "duplexkv.h")).read()
     codes = {k: int(v) for k, v in re.findall(r"#define\s+(KV_E?[A-Z]+)\s+\(?(-?\d+)\)?", text)}
     for name in ("KV_OK", "KV_EINVAL", "KV_ERANGE", "KV_EDUP", "KV_EOVERLAP", "KV_ENOMEM",
-                 "KV_EHIP", "KV_EUNSUP"):
+                 "KV_EHIP", "KV_EUNSUP", "KV_ENOSPC"):
         assert codes[name] == getattr(B, name)
-    assert (B.KV_OK, B.KV_EINVAL, B.KV_ERANGE, B.KV_EDUP, B.KV_EOVERLAP) == \
-           (O.OK, O.EINVAL, O.ERANGE, O.EDUP, O.EOVERLAP)
-    for c in range(-7, 1):
+    assert (B.KV_OK, B.KV_EINVAL, B.KV_ERANGE, B.KV_EDUP, B.KV_EOVERLAP, B.KV_ENOSPC) == \
+           (O.OK, O.EINVAL, O.ERANGE, O.EDUP, O.EOVERLAP, O.ENOSPC)
+    states = {k: int(v) for k, v in re.findall(r"#define\s+(KV_BLOCK_[A-Z]+)\s+(\d+)", text)}
+    assert (states["KV_BLOCK_DIRTY"], states["KV_BLOCK_FULL"], states["KV_BLOCK_SYNCED"], states["KV_BLOCK_HOST"]) == \
+           (O.DIRTY, O.FULL, O.SYNCED, O.HOST) == (B.KV_BLOCK_DIRTY, B.KV_BLOCK_FULL, B.KV_BLOCK_SYNCED, B.KV_BLOCK_HOST)
+    for c in range(-8, 1):
         assert B.kv_strerror(c) != "unknown code"
     assert B.kv_strerror(-99) == "unknown code"
 
@@ -105,3 +108,6 @@ def test_create_fails_loudly_without_gpu_or_with_bad_arguments():
     assert B.lib.kv_wait(None) == B.KV_EINVAL
     assert B.lib.kv_rotate(None, None, None, 0, None, None, 0) == B.KV_EINVAL
     assert B.lib.kv_destroy(None) == B.KV_EINVAL
+    assert B.lib.kv_table_create(ctypes.byref(handle), None, 4) == B.KV_EINVAL
+    assert B.lib.kv_table_rotate(None, None, 0, None, 0) == B.KV_EINVAL
+    assert B.lib.kv_table_destroy(None) == B.KV_EINVAL
