@@ -16,7 +16,11 @@
  * how the bytes move, never which bytes, so the oracle is a memcpy per segment
  * in list order, with no blocking, fusion or reordering.
  *
- * HBM layout  : [layer][K|V][block][token][kv_head][dim]
+ * HBM layouts : 0 = layer-first [layer][K|V][block][token][kv_head][dim]
+ *               1 = block-first [block][layer][K|V][token][kv_head][dim], the
+ *                   cache arrangement Section 4.3.2 proposes ("Block-first
+ *                   layout and batched KV transfers": all layers of a block
+ *                   contiguous, stride between blocks N_L x S_seg)
  * Host layouts: 0 = block-first [slot][layer][K|V][token][kv_head][dim]
  *                   (all layers of a block contiguous, the arrangement of
  *                   Section 4.3.2 "Block-first layout")
@@ -51,13 +55,15 @@ typedef struct {
     int32_t n_hbm_blocks;
     int32_t n_host_slots;
     int32_t host_layout;  /* 0 block-first, 1 layer-first */
+    int32_t hbm_layout;   /* 0 layer-first, 1 block-first */
 } okv_shape;
 
 static int shape_ok(const okv_shape *s)
 {
     return s && s->n_layers > 0 && s->n_kv_heads > 0 && s->head_dim > 0 &&
            s->block_size > 0 && s->elem_bytes > 0 && s->n_hbm_blocks > 0 &&
-           s->n_host_slots > 0 && (s->host_layout == 0 || s->host_layout == 1);
+           s->n_host_slots > 0 && (s->host_layout == 0 || s->host_layout == 1) &&
+           (s->hbm_layout == 0 || s->hbm_layout == 1);
 }
 
 /* Segment: P tokens x per-token bytes of one plane (Section 4.3.1, S_seg = P x C
@@ -88,6 +94,9 @@ uint64_t okv_pool_bytes(const okv_shape *s)
 uint64_t okv_hbm_offset(const okv_shape *s, int32_t l, int32_t kv, int32_t b)
 {
     uint64_t plane = (uint64_t)l * 2u + (uint64_t)kv;
+    uint64_t n_planes = 2u * (uint64_t)s->n_layers;
+    if (s->hbm_layout == 1)
+        return ((uint64_t)b * n_planes + plane) * okv_seg_bytes(s);
     return (plane * (uint64_t)s->n_hbm_blocks + (uint64_t)b) * okv_seg_bytes(s);
 }
 

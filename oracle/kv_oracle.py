@@ -21,13 +21,14 @@ _LIB = os.path.join(_HERE, "libduplexkv_oracle.so")
 
 OK, EINVAL, ERANGE, EDUP, EOVERLAP, ENOSPC = 0, -1, -2, -3, -4, -8
 NONE, DIRTY, FULL, SYNCED, HOST = 0, 1, 2, 3, 4   # block states of the table
-BLOCK_FIRST, LAYER_FIRST = 0, 1
+BLOCK_FIRST, LAYER_FIRST = 0, 1            # host pool layouts
+HBM_LAYER_FIRST, HBM_BLOCK_FIRST = 0, 1    # cache layouts
 
 
 class OkvShape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes",
-        "n_hbm_blocks", "n_host_slots", "host_layout")]
+        "n_hbm_blocks", "n_host_slots", "host_layout", "hbm_layout")]
 
 
 def build(force: bool = False) -> str:
@@ -88,16 +89,16 @@ def lib() -> C.CDLL:
 
 
 def make_shape(n_layers, n_kv_heads, head_dim, block_size, n_hbm_blocks, n_host_slots,
-               elem_bytes=2, host_layout=BLOCK_FIRST) -> OkvShape:
+               elem_bytes=2, host_layout=BLOCK_FIRST, hbm_layout=HBM_LAYER_FIRST) -> OkvShape:
     return OkvShape(n_layers, n_kv_heads, head_dim, block_size, elem_bytes,
-                    n_hbm_blocks, n_host_slots, host_layout)
+                    n_hbm_blocks, n_host_slots, host_layout, hbm_layout)
 
 
-def shape_of(kvshape, host_layout=BLOCK_FIRST) -> OkvShape:
+def shape_of(kvshape, host_layout=BLOCK_FIRST, hbm_layout=HBM_LAYER_FIRST) -> OkvShape:
     """From any object with the KV shape attributes (e.g. workloads.KVShape)."""
     return make_shape(kvshape.n_layers, kvshape.n_kv_heads, kvshape.head_dim,
                       kvshape.block_size, kvshape.n_hbm_blocks, kvshape.n_host_slots,
-                      kvshape.elem_bytes, host_layout)
+                      kvshape.elem_bytes, host_layout, hbm_layout)
 
 
 def _ids(a):

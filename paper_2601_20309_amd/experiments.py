@@ -4,6 +4,7 @@
   python -m paper_2601_20309_amd.experiments configs       # configs[1..3] of the benchmark spec, default path
   python -m paper_2601_20309_amd.experiments interference  # configs[4]: rotation beside a decode reader
   python -m paper_2601_20309_amd.experiments reader        # the decode reader alone (profiling target)
+  python -m paper_2601_20309_amd.experiments eager         # a preemption with and without eager block rotation
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -255,6 +256,45 @@ def reader():
     eng.kv_destroy()
 
 
+def eager():
+    """What eager block rotation buys at a preemption (Section 4.3.2): 8 requests
+    of 4096 tokens leave while 8 others come back, Llama-3-8B shape, with and
+    without the background copies having been issued beforehand."""
+    shape = W.SHAPES["interference"]
+    cache = _cache(shape)
+    print("\n| eager step before the rotation | blocks copied out at preemption | dropped without a copy | "
+          "blocks swapped in | rotation ms | out GiB | in GiB |")
+    print("|---|---|---|---|---|---|---|")
+    for do_eager in (False, True):
+        eng = B.Engine(B.make_config(shape), cache.data_ptr())
+        tab = B.Table(eng, 32)
+        blk = B.kv_block_bytes(eng.cfg)
+        for r in range(16):
+            assert tab.kv_table_append(r, 4096 - 5)[0] == 0      # 255 full blocks + a dirty tail
+        assert tab.kv_table_rotate(list(range(8, 16)), []) == 0   # 8 requests wait in DRAM
+        assert eng.kv_wait() == 0
+        t_eager = 0.0
+        if do_eager:
+            t0 = time.perf_counter()
+            rc, n = tab.kv_table_eager(1 << 30)
+            assert rc == 0 and eng.kv_wait() == 0
+            t_eager = (time.perf_counter() - t0) * 1e3
+        c0 = tab.kv_table_get_counts()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        assert tab.kv_table_rotate(list(range(8)), list(range(8, 16))) == 0
+        assert eng.kv_wait() == 0
+        ms = (time.perf_counter() - t0) * 1e3
+        c1 = tab.kv_table_get_counts()
+        st = eng.kv_last_stats()
+        label = f"yes ({n} blocks, {t_eager:.1f} ms in the background)" if do_eager else "no"
+        print(f"| {label} | {c1['copied_preempt'] - c0['copied_preempt']} | {c1['dropped_synced'] - c0['dropped_synced']} | "
+              f"{c1['swapped_in'] - c0['swapped_in']} | {ms:.2f} | {st['bytes_out'] / 2**30:.3f} | {st['bytes_in'] / 2**30:.3f} |")
+        tab.kv_table_destroy()
+        eng.kv_destroy()
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "configs"
-    {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader}[what]()
+    {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
+     "eager": eager}[what]()

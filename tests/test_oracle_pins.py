@@ -453,3 +453,79 @@ def test_read_checksum_against_numpy_and_closed_form(name):
     assert twice == (2 * got1) % (1 << 64)
     assert O.read_checksum(s, u8(cache), [])[1] == 0
     assert O.read_checksum(s, u8(cache), [sh.n_hbm_blocks])[0] == O.ERANGE
+
+
+# ---- block-first cache layout (Section 4.3.2, "Block-first layout and batched KV transfers") ----
+
+def elem_off_hbm_block_first(sh, l, kv, b, t, h, d):
+    return (((((b * sh.n_layers + l) * 2 + kv) * sh.block_size + t) * sh.n_kv_heads + h)
+            * sh.head_dim + d)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name", ["tiny", "ragged"])
+def test_block_first_cache_brute_force_and_indexing(name, layout):
+    sh = W.SHAPES[name]
+    rot = W.config_rotation(name)
+    if name == "tiny":
+        rot = W.Rotation(rot.out_ids[:3], rot.out_slots[:3], rot.in_ids[:3], rot.in_slots[:3])
+    cache, pool = V.make_images(sh, layout, rot, W.value_seed(name), hbm_layout=1)
+    s = O.shape_of(sh, layout, O.HBM_BLOCK_FIRST)
+    c, p = cache.copy(), pool.copy()
+    assert O.rotate(s, u8(c), u8(p), rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots) == O.OK
+    # six loops over elements, with the block-first element offset written out
+    cb, pb = cache.copy(), pool.copy()
+    idx = lambda: itertools.product(range(sh.n_layers), range(2), range(sh.block_size),
+                                    range(sh.n_kv_heads), range(sh.head_dim))
+    for b, sl in zip(rot.out_ids, rot.out_slots):
+        for l, kv, t, h, d in idx():
+            pb[elem_off_pool(sh, layout, l, kv, int(sl), t, h, d)] = \
+                cache[elem_off_hbm_block_first(sh, l, kv, int(b), t, h, d)]
+    for b, sl in zip(rot.in_ids, rot.in_slots):
+        for l, kv, t, h, d in idx():
+            cb[elem_off_hbm_block_first(sh, l, kv, int(b), t, h, d)] = \
+                pool[elem_off_pool(sh, layout, l, kv, int(sl), t, h, d)]
+    assert np.array_equal(c, cb) and np.array_equal(p, pb)
+    # the same through array indexing on the block-first view
+    ce, pe = V.expected_by_indexing(sh, layout, cache, pool, rot, hbm_layout=1)
+    assert np.array_equal(c, ce) and np.array_equal(p, pe)
+    # and it is not what the layer-first reading of the same bytes gives
+    s0 = O.shape_of(sh, layout, O.HBM_LAYER_FIRST)
+    c0, p0 = cache.copy(), pool.copy()
+    O.rotate(s0, u8(c0), u8(p0), rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots)
+    assert not np.array_equal(p0, p)
+
+
+def test_block_first_cache_strides_match_the_paper():
+    """With the block-first layout the stride between blocks i and j is
+    (j - i) x N_L x S_seg and a block is one contiguous region (4 MB for the
+    worked example); with the layer-first layout it is (j - i) x S_seg."""
+    g = read_golden("paper_worked_sizes.txt")
+    for hbm_layout, stride in [(O.HBM_BLOCK_FIRST, g["n_layers"] * g["segment_k_plus_v"]),
+                               (O.HBM_LAYER_FIRST, g["segment_k_plus_v"] // 2)]:
+        s = O.make_shape(g["n_layers"], g["n_kv_heads"], g["head_dim"], g["block_size"], 16, 16,
+                         elem_bytes=g["elem_bytes"], hbm_layout=hbm_layout)
+        assert O.hbm_offset(s, 0, 0, 7) - O.hbm_offset(s, 0, 0, 3) == 4 * stride
+    s = O.make_shape(g["n_layers"], g["n_kv_heads"], g["head_dim"], g["block_size"], 16, 16,
+                     elem_bytes=g["elem_bytes"], hbm_layout=O.HBM_BLOCK_FIRST)
+    offs = sorted(O.hbm_offset(s, l, kv, 5) for l in range(g["n_layers"]) for kv in range(2))
+    assert offs[0] == 5 * g["block_all_layers"]
+    assert offs == list(range(offs[0], offs[0] + g["block_all_layers"], O.seg_bytes(s)))
+    # offsets still tile the image exactly
+    sh = W.SHAPES["ragged"]
+    s = O.shape_of(sh, O.BLOCK_FIRST, O.HBM_BLOCK_FIRST)
+    h = {O.hbm_offset(s, l, kv, b) for l in range(sh.n_layers) for kv in range(2) for b in range(sh.n_hbm_blocks)}
+    assert h == set(range(0, O.cache_bytes(s), O.seg_bytes(s)))
+
+
+def test_block_first_cache_checksum_and_bad_layout():
+    sh = W.SHAPES["ragged"]
+    rot = W.config_rotation("ragged")
+    cache, _ = V.make_images(sh, O.BLOCK_FIRST, rot, 9, hbm_layout=1)
+    s = O.shape_of(sh, O.BLOCK_FIRST, O.HBM_BLOCK_FIRST)
+    ids = np.concatenate([rot.out_ids, rot.in_ids])
+    rc, got = O.read_checksum(s, u8(cache), ids)
+    blocks = np.ascontiguousarray(V.hbm_view(sh, cache, 1)[:, :, ids])
+    assert rc == O.OK and got == int(blocks.view("<u4").sum(dtype=np.uint64))
+    bad = O.make_shape(2, 2, 64, 16, 64, 32, hbm_layout=2)
+    assert O.validate(bad, [1], [1], None, None) == O.EINVAL
