@@ -12,7 +12,10 @@
  * in one plane are one "segment", the largest contiguous unit in HBM:
  *   seg   = block_size * n_kv_heads * head_dim * elem_bytes
  *   block = 2 * n_layers * seg          (what one block costs on the link)
- * HBM layout : [layer][K|V][block][token][kv_head][dim]      (K = 0, V = 1)
+ * HBM layout : KV_HBM_LAYER_FIRST [layer][K|V][block][token][kv_head][dim] (default;
+ *              K = 0, V = 1), or KV_HBM_BLOCK_FIRST [block][layer][K|V][token]...,
+ *              the cache arrangement Section 4.3.2 proposes (a block is one
+ *              contiguous region, stride between blocks N_L x S_seg per plane pair).
  * Host pool  : KV_HOST_BLOCK_FIRST [slot][layer][K|V][token][kv_head][dim]
  *              (all layers of a block contiguous: the "block-first layout" of
  *              Section 4.3.2) or KV_HOST_LAYER_FIRST [layer][K|V][slot][...].
@@ -51,12 +54,18 @@ extern "C" {
 #define KV_HOST_BLOCK_FIRST 0
 #define KV_HOST_LAYER_FIRST 1
 
+/* ---- cache layouts ---- */
+#define KV_HBM_LAYER_FIRST 0
+#define KV_HBM_BLOCK_FIRST 1
+
 /* ---- transfer paths ---- */
 #define KV_PATH_AUTO        0  /* engine picks: FUSED for a rotation, ZEROCOPY for one direction */
 #define KV_PATH_SDMA_STAGED 1  /* pack kernel -> staging in HBM -> hipMemcpyAsync (DMA engines), and the mirror */
 #define KV_PATH_ZEROCOPY    2  /* one kernel per direction, each on its own stream, reading / writing host memory directly */
 #define KV_PATH_NAIVE       3  /* one hipMemcpyAsync per segment: the baseline of Section 4.3.1, for the benchmark ladder */
 #define KV_PATH_FUSED       4  /* one kernel moves both directions, interleaved 1:1 per thread */
+#define KV_PATH_DMA_BLOCKS  5  /* one hipMemcpyAsync per block (runs of consecutive ids and slots merge): the
+                                  "merged segments" design of Section 4.3.2; needs KV_HBM_BLOCK_FIRST and KV_HOST_BLOCK_FIRST */
 
 typedef struct kv_engine kv_engine; /* opaque, owned by the library */
 
@@ -74,7 +83,7 @@ typedef struct {
     int32_t max_copy_wgs;  /* workgroups a copy kernel may occupy; 0 = engine picks */
     int32_t vecs_per_lane; /* 16-byte vectors each lane keeps in flight per direction in the link kernels: 0 = engine picks, else 1, 2, 4 or 8 */
     int32_t wg_lanes;      /* lanes per workgroup of the link kernels: 0 = engine picks, else a multiple of 64 up to 1024 */
-    int32_t reserved;      /* must be 0 */
+    int32_t hbm_layout;    /* KV_HBM_* */
     uint64_t staging_bytes;/* SDMA_STAGED: bytes of HBM staging per direction = largest chunk; 0 = engine picks (256 MiB) */
 } kv_config;
 
@@ -108,7 +117,7 @@ int kv_validate(const kv_config *cfg,
 
 /*
  * Create an engine on the current HIP device.
- *  hbm_cache  : device pointer, kv_cache_bytes(cfg) bytes in the HBM layout above;
+ *  hbm_cache  : device pointer, kv_cache_bytes(cfg) bytes in the configured HBM layout;
  *               owned by the caller and must outlive the engine.
  *  host_pool  : NULL = the engine allocates (and owns) a pinned pool of
  *               kv_pool_bytes(cfg); otherwise a caller-owned pinned, device-mapped

@@ -20,8 +20,10 @@ KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP
     0, -1, -2, -3, -4, -5, -6, -7, -8
 KV_BLOCK_DIRTY, KV_BLOCK_FULL, KV_BLOCK_SYNCED, KV_BLOCK_HOST = 1, 2, 3, 4
 KV_HOST_BLOCK_FIRST, KV_HOST_LAYER_FIRST = 0, 1
-KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSED = 0, 1, 2, 3, 4
-PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"}
+KV_HBM_LAYER_FIRST, KV_HBM_BLOCK_FIRST = 0, 1
+KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSED, KV_PATH_DMA_BLOCKS = \
+    0, 1, 2, 3, 4, 5
+PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused", 5: "dma_blocks"}
 
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
            "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
@@ -33,7 +35,7 @@ EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", 
 class kv_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes", "n_hbm_blocks",
-        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "vecs_per_lane", "wg_lanes", "reserved")] + \
+        "n_host_slots", "host_layout", "path", "chunk_layers", "max_copy_wgs", "vecs_per_lane", "wg_lanes", "hbm_layout")] + \
         [("staging_bytes", C.c_uint64)]
 
 
@@ -113,11 +115,11 @@ lib = _load()
 
 
 def make_config(shape, host_layout=KV_HOST_BLOCK_FIRST, path=KV_PATH_AUTO, chunk_layers=0,
-                max_copy_wgs=0, staging_bytes=0, vecs_per_lane=0, wg_lanes=0) -> kv_config:
+                max_copy_wgs=0, staging_bytes=0, vecs_per_lane=0, wg_lanes=0, hbm_layout=KV_HBM_LAYER_FIRST) -> kv_config:
     """kv_config from any object carrying the KV shape attributes."""
     return kv_config(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
                      shape.elem_bytes, shape.n_hbm_blocks, shape.n_host_slots, host_layout, path,
-                     chunk_layers, max_copy_wgs, vecs_per_lane, wg_lanes, 0, staging_bytes)
+                     chunk_layers, max_copy_wgs, vecs_per_lane, wg_lanes, hbm_layout, staging_bytes)
 
 
 def _ids(a):

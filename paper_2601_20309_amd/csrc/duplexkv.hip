@@ -12,6 +12,9 @@
 //                for the link itself.
 //   NAIVE        one hipMemcpyAsync per segment, the per-segment baseline of
 //                Section 4.3.1 of the paper, kept for the benchmark ladder.
+//   DMA_BLOCKS   block-first cache and block-first pool: a block is one
+//                contiguous region on both sides, one hipMemcpyAsync per block
+//                (the paper's "merged segments"), runs of consecutive pairs merged.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -45,12 +48,15 @@ bool config_ok(const kv_config *c)
         c->elem_bytes <= 0 || c->n_hbm_blocks <= 0 || c->n_host_slots <= 0)
         return false;
     if (c->host_layout != KV_HOST_BLOCK_FIRST && c->host_layout != KV_HOST_LAYER_FIRST) return false;
-    if (c->path < KV_PATH_AUTO || c->path > KV_PATH_FUSED) return false;
+    if (c->path < KV_PATH_AUTO || c->path > KV_PATH_DMA_BLOCKS) return false;
+    if (c->hbm_layout != KV_HBM_LAYER_FIRST && c->hbm_layout != KV_HBM_BLOCK_FIRST) return false;
+    if (c->path == KV_PATH_DMA_BLOCKS &&
+        (c->hbm_layout != KV_HBM_BLOCK_FIRST || c->host_layout != KV_HOST_BLOCK_FIRST))
+        return false;
     if (c->chunk_layers < 0 || c->max_copy_wgs < 0) return false;
     if (c->vecs_per_lane != 0 && c->vecs_per_lane != 1 && c->vecs_per_lane != 2 && c->vecs_per_lane != 4 &&
         c->vecs_per_lane != 8)
         return false;
-    if (c->reserved != 0) return false;
     if (c->wg_lanes < 0 || c->wg_lanes > dkv::kMaxThreads || c->wg_lanes % 64 != 0) return false;
     // sizes must stay far inside 64 bits
     const long double cache = 2.0L * c->n_layers * (long double)c->n_hbm_blocks * c->block_size *
@@ -242,13 +248,24 @@ void launch_move(int u, int vec, int wgs, int lanes, hipStream_t s, const MovePa
     }
 }
 
+void hbm_strides(const kv_engine *e, uint64_t &plane_stride, uint64_t &block_stride)
+{
+    if (e->cfg.hbm_layout == KV_HBM_BLOCK_FIRST) {
+        plane_stride = e->seg;
+        block_stride = (uint64_t)e->n_planes * e->seg;
+    } else {
+        plane_stride = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+        block_stride = e->seg;
+    }
+}
+
 // Fills the fields common to every launch; `u` = vectors per lane per tile.
 MoveParams base_params(const kv_engine *e, int u, int lanes = dkv::kThreads)
 {
     MoveParams p{};
     p.hbm = e->hbm;
     p.seg_bytes = e->seg;
-    p.hbm_plane_stride = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    hbm_strides(e, p.hbm_plane_stride, p.hbm_block_stride);
     p.plane0 = 0;
     p.n_planes = e->n_planes;
     p.vec_per_seg = (uint32_t)(e->seg / (uint64_t)e->vec);
@@ -449,7 +466,8 @@ int run_naive(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, co
 {
     uint64_t ss, ps;
     pool_strides(e, ss, ps);
-    const uint64_t hps = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    uint64_t hps, hbs;
+    hbm_strides(e, hps, hbs);
     if (no > 0 && mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
     if (ni > 0 && mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
     const int32_t nmax = std::max(no, ni);
@@ -457,17 +475,57 @@ int run_naive(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, co
         for (uint32_t pl = 0; pl < e->n_planes; pl++) {
             if (i < no) {
                 HIPTRY(e, hipMemcpyAsync(e->pool + (uint64_t)os[i] * ss + pl * ps,
-                                         e->hbm + pl * hps + (uint64_t)oi[i] * e->seg, e->seg,
+                                         e->hbm + pl * hps + (uint64_t)oi[i] * hbs, e->seg,
                                          hipMemcpyDeviceToHost, e->s_out));
             }
             if (i < ni) {
-                HIPTRY(e, hipMemcpyAsync(e->hbm + pl * hps + (uint64_t)ii[i] * e->seg,
+                HIPTRY(e, hipMemcpyAsync(e->hbm + pl * hps + (uint64_t)ii[i] * hbs,
                                          e->pool + (uint64_t)is[i] * ss + pl * ps, e->seg,
                                          hipMemcpyHostToDevice, e->s_in));
             }
         }
     }
     e->acc.n_launches += (int32_t)(((int64_t)no + ni) * e->n_planes);
+    if (no > 0) {
+        HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
+        e->b_o1 = e->ev_o1;
+        e->out_pending = true;
+    }
+    if (ni > 0) {
+        HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
+        e->b_i1 = e->ev_i1;
+        e->in_pending = e->in_dirty = true;
+    }
+    return KV_OK;
+}
+
+// ---- DMA_BLOCKS: one copy per block, both sides block-first -----------------------
+int run_dma_blocks(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+                   const int32_t *is, int32_t ni)
+{
+    const uint64_t bb = e->block_bytes;
+    if (no > 0 && mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
+    if (ni > 0 && mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
+    int32_t a = 0, b = 0, n_copies = 0;
+    while (a < no || b < ni) {  // alternate so both streams fill together
+        if (a < no) {
+            int32_t r = a + 1;  // run in which block ids and slots both advance by one
+            while (r < no && oi[r] == oi[r - 1] + 1 && os[r] == os[r - 1] + 1) r++;
+            HIPTRY(e, hipMemcpyAsync(e->pool + (uint64_t)os[a] * bb, e->hbm + (uint64_t)oi[a] * bb,
+                                     (uint64_t)(r - a) * bb, hipMemcpyDeviceToHost, e->s_out));
+            a = r;
+            n_copies++;
+        }
+        if (b < ni) {
+            int32_t r = b + 1;
+            while (r < ni && ii[r] == ii[r - 1] + 1 && is[r] == is[r - 1] + 1) r++;
+            HIPTRY(e, hipMemcpyAsync(e->hbm + (uint64_t)ii[b] * bb, e->pool + (uint64_t)is[b] * bb,
+                                     (uint64_t)(r - b) * bb, hipMemcpyHostToDevice, e->s_in));
+            b = r;
+            n_copies++;
+        }
+    }
+    e->acc.n_launches += n_copies;
     if (no > 0) {
         HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
         e->b_o1 = e->ev_o1;
@@ -690,6 +748,8 @@ int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, con
     open_batch(e);
     if (path == KV_PATH_NAIVE) {
         rc = run_naive(e, oi, os, no, ii, is, ni);
+    } else if (path == KV_PATH_DMA_BLOCKS) {
+        rc = run_dma_blocks(e, oi, os, no, ii, is, ni);
     } else {
         int k;
         rc = acquire_ring(e, k);
@@ -1050,8 +1110,7 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
     p.hbm = e->hbm;
     p.ids = e->read_ids;
     p.acc = e->read_acc;
-    p.seg_bytes = e->seg;
-    p.hbm_plane_stride = (uint64_t)e->cfg.n_hbm_blocks * e->seg;
+    hbm_strides(e, p.hbm_plane_stride, p.hbm_block_stride);
     p.n = (uint32_t)n;
     p.n_planes = e->n_planes;
     p.vec_per_seg = (uint32_t)(e->seg / 16);
@@ -1132,7 +1191,8 @@ int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
     if (!out) return KV_EINVAL;
     *out = nullptr;
     if (!e || max_requests <= 0) return KV_EINVAL;
-    if (e->cfg.path == KV_PATH_SDMA_STAGED || e->cfg.path == KV_PATH_NAIVE) return KV_EUNSUP;
+    if (e->cfg.path == KV_PATH_SDMA_STAGED || e->cfg.path == KV_PATH_NAIVE || e->cfg.path == KV_PATH_DMA_BLOCKS)
+        return KV_EUNSUP;
     kv_table *t = new (std::nothrow) kv_table;
     if (!t) return KV_ENOMEM;
     t->e = e;

@@ -32,7 +32,7 @@ struct DirDesc {
 };
 
 // Addressing (Section 4.3.1 of the paper: layer x block x segment):
-//   HBM  segment (plane, id)   at hbm + plane * hbm_plane_stride + id * seg_bytes
+//   HBM  segment (plane, id)   at hbm + plane * hbm_plane_stride + id * hbm_block_stride
 //   far  segment (plane, slot) at far + slot * far_slot_stride + plane * far_plane_stride
 // `plane` = layer * 2 + (0 for K, 1 for V).
 struct MoveParams {
@@ -40,7 +40,8 @@ struct MoveParams {
     uint8_t *far_out;  // destination of the out direction (host pool or staging)
     uint8_t *far_in;   // source of the in direction
     uint64_t seg_bytes;
-    uint64_t hbm_plane_stride;
+    uint64_t hbm_plane_stride;  // layer-first cache: blocks * seg; block-first cache: seg
+    uint64_t hbm_block_stride;  // layer-first cache: seg;          block-first cache: planes * seg
     uint64_t far_slot_stride_out, far_plane_stride_out;
     uint64_t far_slot_stride_in, far_plane_stride_in;
     uint32_t plane0;         // first plane this launch covers
@@ -87,7 +88,7 @@ __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d,
     pl += p.plane0;
     const uint32_t id = (uint32_t)ids[i];
     const uint32_t slot = d.iota ? i : (uint32_t)slots[i];
-    hbm_off = (uint64_t)pl * p.hbm_plane_stride + (uint64_t)id * p.seg_bytes + (uint64_t)tin * tile_bytes;
+    hbm_off = (uint64_t)pl * p.hbm_plane_stride + (uint64_t)id * p.hbm_block_stride + (uint64_t)tin * tile_bytes;
     far_off = (uint64_t)slot * slot_stride + (uint64_t)pl * plane_stride + (uint64_t)tin * tile_bytes;
 }
 
@@ -264,7 +265,7 @@ struct ReadParams {
     const uint8_t *hbm;
     const int32_t *ids;
     unsigned long long *acc;  // one 64-bit accumulator in device memory
-    uint64_t seg_bytes;
+    uint64_t hbm_block_stride;
     uint64_t hbm_plane_stride;
     uint32_t n;              // blocks
     uint32_t n_planes;
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
         const uint32_t pl = segidx / p.n;
         const uint32_t i = segidx - pl * p.n;
         const u32x4 *src = reinterpret_cast<const u32x4 *>(
-            p.hbm + (uint64_t)pl * p.hbm_plane_stride + (uint64_t)(uint32_t)p.ids[i] * p.seg_bytes);
+            p.hbm + (uint64_t)pl * p.hbm_plane_stride + (uint64_t)(uint32_t)p.ids[i] * p.hbm_block_stride);
         const uint32_t v0 = tin * (kThreads * U) + tid;
         u32x4 v[U];
 #pragma unroll

@@ -16,7 +16,7 @@ class GpuCase:
                  **cfgkw):
         self.shape, self.layout = shape, layout
         self.cfg = B.make_config(shape, layout, path, **cfgkw)
-        self.oshape = O.shape_of(shape, layout)
+        self.oshape = O.shape_of(shape, layout, cfgkw.get("hbm_layout", 0))
         self.ref_cache = cache_u16.copy()
         self.ref_pool = pool_u16.copy()
         self.dev_cache = torch.from_numpy(cache_u16.view(np.int16).copy()).cuda()
@@ -77,7 +77,7 @@ def make_case(name_or_shape, layout, path, rot=None, seed=None, **kw):
     else:
         shape = name_or_shape
         seed = 1234 if seed is None else seed
-    cache, pool = V.make_images(shape, layout, rot, seed)
+    cache, pool = V.make_images(shape, layout, rot, seed, hbm_layout=kw.get("hbm_layout", 0))
     return GpuCase(shape, layout, path, cache, pool, **kw), rot
 
 

@@ -54,7 +54,7 @@ def test_sizes_agree_with_oracle(name):
 
 def test_bad_config_sizes_are_zero_and_validate_rejects():
     sh = W.SHAPES["tiny"]
-    for field, val in [("n_layers", 0), ("host_layout", 2), ("path", 9), ("vecs_per_lane", 3), ("reserved", 1), ("wg_lanes", 100), ("wg_lanes", 2048),
+    for field, val in [("n_layers", 0), ("host_layout", 2), ("path", 9), ("vecs_per_lane", 3), ("hbm_layout", 2), ("path", 6), ("wg_lanes", 100), ("wg_lanes", 2048),
                        ("elem_bytes", -2), ("chunk_layers", -1)]:
         cfg = B.make_config(sh)
         setattr(cfg, field, val)

@@ -199,3 +199,40 @@ def test_workgroup_width(lanes):
         case.rotate(rot)
         case.check()
         case.close()
+
+
+BF = dict(hbm_layout=B.KV_HBM_BLOCK_FIRST)
+
+
+@pytest.mark.parametrize("path", PATHS + [B.KV_PATH_DMA_BLOCKS])
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name", ["tiny", "ragged", "small8b"])
+def test_block_first_cache(name, layout, path):
+    """The cache arrangement the paper proposes: [block][layer][K|V]..."""
+    if path == B.KV_PATH_DMA_BLOCKS and layout != B.KV_HOST_BLOCK_FIRST:
+        with pytest.raises(B.KVError):          # per-block copies need both sides block-first
+            make_case(name, layout, path, **BF)
+        return
+    case, rot = make_case(name, layout, path, **BF)
+    case.rotate(rot)
+    case.check()
+    case.rotate(rot.inverse())
+    case.check()
+    case.close()
+
+
+def test_dma_blocks_merges_runs_and_needs_block_first_cache():
+    sh = W.SHAPES["small8b"]
+    rng = np.random.default_rng(2)
+    # out: blocks 10..41 -> slots 0..31 (one run); in: slots 64..95 -> blocks 100..131 in two runs
+    out_ids, out_slots = np.arange(10, 42), np.arange(0, 32)
+    in_ids = np.concatenate([np.arange(100, 116), np.arange(200, 216)])
+    in_slots = np.arange(64, 96)
+    rot = W.Rotation(*(a.astype(np.int32) for a in (out_ids, out_slots, in_ids, in_slots)))
+    case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_DMA_BLOCKS, rot=rot, **BF)
+    case.rotate(rot)
+    case.check()
+    assert case.eng.kv_last_stats()["n_launches"] == 1 + 2
+    case.close()
+    with pytest.raises(B.KVError):
+        make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_DMA_BLOCKS, rot=rot)     # layer-first cache

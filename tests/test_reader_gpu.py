@@ -54,3 +54,13 @@ def test_reader_runs_beside_a_rotation(path):
     assert got2 == (want2 * 2) % (1 << 64)
     case.check()
     case.close()
+
+
+def test_reader_on_block_first_cache():
+    case, rot = make_case("small8b", B.KV_HOST_BLOCK_FIRST, B.KV_PATH_AUTO, hbm_layout=B.KV_HBM_BLOCK_FIRST)
+    ids = np.random.default_rng(4).permutation(case.shape.n_hbm_blocks)[:100]
+    rc, want = O.read_checksum(case.oshape, case.ref_cache.view(np.uint8), ids)
+    assert case.eng.kv_reader_start(ids, 2) == 0
+    rc, got, _ = case.eng.kv_reader_wait()
+    assert rc == 0 and got == (2 * want) % (1 << 64)
+    case.close()
