@@ -5,6 +5,8 @@
   python -m paper_2601_20309_amd.experiments interference  # configs[4]: rotation beside a decode reader
   python -m paper_2601_20309_amd.experiments reader        # the decode reader alone (profiling target)
   python -m paper_2601_20309_amd.experiments eager         # a preemption with and without eager block rotation
+  python -m paper_2601_20309_amd.experiments layouts       # layer-first against block-first cache layout
+  python -m paper_2601_20309_amd.experiments linksweep     # bandwidth against segment size, copies and kernels
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -107,6 +109,128 @@ def ladder(name="qwen25_32b"):
     print("|---|---|---|---|")
     for label, d, du, h, hu, ms in rows:
         print(f"| {label} | {d:.2f} ({du}) | {h:.2f} ({hu}) | {ms:.2f} |")
+
+
+def layouts(name="qwen25_32b"):
+    """Layer-first cache (this build's default) against the block-first cache the
+    paper proposes, same workload as the ladder: rotation paths and the reader."""
+    shape = W.SHAPES[name]
+    cache = _cache(shape)
+    rot = W.config_rotation(name)
+    print(f"\n{name}: {len(rot.out_ids)} scattered blocks each way\n")
+    print("| cache layout | method | D2H GB/s | H2D GB/s | E2E ms |")
+    print("|---|---|---|---|---|")
+    for hbm, hname in ((B.KV_HBM_LAYER_FIRST, "layer-first"), (B.KV_HBM_BLOCK_FIRST, "block-first")):
+        plans = [("fused duplex kernel", B.KV_PATH_FUSED, False)]
+        if hbm == B.KV_HBM_BLOCK_FIRST:
+            plans += [("one DMA copy per block, one direction at a time (the paper's MS)", B.KV_PATH_DMA_BLOCKS, True),
+                      ("one DMA copy per block, both directions at once", B.KV_PATH_DMA_BLOCKS, False)]
+        else:
+            plans += [("pack kernel + one DMA copy per block, one direction at a time", B.KV_PATH_SDMA_STAGED, True),
+                      ("pack kernel + one DMA copy per block, both directions at once", B.KV_PATH_SDMA_STAGED, False)]
+        for label, path, serial in plans:
+            eng = B.Engine(B.make_config(shape, path=path, hbm_layout=hbm), cache.data_ptr())
+            blk = B.kv_block_bytes(eng.cfg)
+            nbytes = len(rot.out_ids) * blk
+            inv = rot.inverse()
+            if serial:
+                to, ti = [], []
+                for i in range(4):
+                    a = rot if i % 2 == 0 else inv
+                    torch.cuda.synchronize(); t0 = time.perf_counter()
+                    assert eng.kv_swap_out(a.out_ids, a.out_slots) == 0 and eng.kv_wait() == 0
+                    t1 = time.perf_counter()
+                    assert eng.kv_swap_in(a.in_slots, a.in_ids) == 0 and eng.kv_wait() == 0
+                    t2 = time.perf_counter()
+                    if i:
+                        to.append((t1 - t0) * 1e3); ti.append((t2 - t1) * 1e3)
+                mo, mi = statistics.median(to), statistics.median(ti)
+                print(f"| {hname} | {label} | {nbytes / mo / 1e6:.2f} (u) | {nbytes / mi / 1e6:.2f} (u) | {mo + mi:.2f} |", flush=True)
+            else:
+                calls = _rot_calls(eng, rot)
+
+                def fn(i):
+                    assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+                ms, _, _ = _time_calls(eng, fn, 4)
+                print(f"| {hname} | {label} | {nbytes / ms / 1e6:.2f} (b) | {nbytes / ms / 1e6:.2f} (b) | {ms:.2f} |", flush=True)
+            eng.kv_destroy()
+    print("\n| cache layout | reader TB/s (all blocks of the cache, plane by plane) |")
+    print("|---|---|")
+    for hbm, hname in ((B.KV_HBM_LAYER_FIRST, "layer-first"), (B.KV_HBM_BLOCK_FIRST, "block-first")):
+        eng = B.Engine(B.make_config(shape, hbm_layout=hbm), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        ids = np.random.default_rng(3).permutation(shape.n_hbm_blocks).astype(np.int32)
+        assert eng.kv_reader_start(ids, 6) == 0
+        rc, _, pm = eng.kv_reader_wait()
+        print(f"| {hname} | {len(ids) * blk / statistics.median(pm[1:]) / 1e9:.2f} |", flush=True)
+        eng.kv_destroy()
+
+
+def linksweep():
+    """Bandwidth against contiguous piece size, the analogue of the paper's link
+    characterisation (Figs. 5 and 8): 256 MiB per direction moved as scattered
+    segments of one size, by one DMA copy per segment and by the gather / scatter
+    kernels; for the copies also the host time to enqueue one against the time
+    the link needs for it."""
+    print("\n| segment | copies per direction | per-copy DMA D2H GB/s | H2D GB/s | enqueue us / copy | "
+          "link us / copy at 57 GB/s | kernel D2H GB/s | kernel H2D GB/s | fused both ways GB/s (sum) |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    total = 256 << 20
+    for seg in [4 << 10, 16 << 10, 32 << 10, 64 << 10, 256 << 10, 1 << 20, 4 << 20, 16 << 20, 64 << 20]:
+        heads = seg // 4096                       # 16 tokens x heads x 128 dims x 2 bytes
+        n = max(1, total // (2 * seg))            # one layer: a block is two segments
+        n_copies = min(2 * n, 4096)
+        n_naive = n_copies // 2
+        nb = max(4 * n, 8)
+        shape = W.KVShape(1, heads, 128, 16, n_hbm_blocks=nb, n_host_slots=2 * n + 2)
+        cache = _cache(shape)
+        rot = W.simple_rotation(shape, n, n, seed=seg)
+        row = [f"{seg >> 10} KiB", str(2 * n_naive)]
+        # one DMA copy per segment
+        eng = B.Engine(B.make_config(shape, path=B.KV_PATH_NAIVE), cache.data_ptr())
+        res = {}
+        for d in ("out", "in"):
+            ts, enq = [], []
+            for i in range(3):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                if d == "out":
+                    assert eng.kv_swap_out(rot.out_ids[:n_naive], rot.out_slots[:n_naive]) == 0
+                else:
+                    assert eng.kv_swap_in(rot.in_slots[:n_naive], rot.in_ids[:n_naive]) == 0
+                t1 = time.perf_counter()
+                assert eng.kv_wait() == 0
+                t2 = time.perf_counter()
+                if i:
+                    ts.append(t2 - t0); enq.append(t1 - t0)
+            res[d] = (2 * n_naive * seg / statistics.median(ts) / 1e9, statistics.median(enq) / (2 * n_naive) * 1e6)
+        eng.kv_destroy()
+        row += [f"{res['out'][0]:.2f}", f"{res['in'][0]:.2f}", f"{(res['out'][1] + res['in'][1]) / 2:.2f}",
+                f"{seg / 57e9 * 1e6:.2f}"]
+        # gather / scatter kernels
+        eng = B.Engine(B.make_config(shape), cache.data_ptr())
+        inv = rot.inverse()
+        for d in ("out", "in", "both"):
+            ts = []
+            for i in range(5):
+                a = rot if i % 2 == 0 else inv
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                if d == "out":
+                    rc = eng.kv_swap_out(a.out_ids, a.out_slots)
+                elif d == "in":
+                    rc = eng.kv_swap_in(a.in_slots, a.in_ids)
+                else:
+                    rc = eng.kv_rotate(a.out_ids, a.out_slots, a.in_ids, a.in_slots)
+                assert rc == 0 and eng.kv_wait() == 0
+                if i:
+                    ts.append(time.perf_counter() - t0)
+            moved = 2 * n * seg * (2 if d == "both" else 1)
+            row.append(f"{moved / statistics.median(ts) / 1e9:.2f}")
+        eng.kv_destroy()
+        print("| " + " | ".join(row) + " |", flush=True)
+        del cache
+        torch.cuda.empty_cache()
 
 
 def configs():
@@ -297,4 +421,5 @@ def eager():
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "configs"
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
-     "eager": eager}[what]()
+     "eager": eager, "layouts": layouts,
+     "linksweep": linksweep}[what]()
