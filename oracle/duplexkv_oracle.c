@@ -602,3 +602,123 @@ int okvt_counts(const okvt *t, int64_t *counts)
     counts[5] = t->swapped_in;
     return OKV_OK;
 }
+
+/* ------------------------------------------------------------------------
+ * Scheduler that decides what rotates: Virtual Lag Time and Largest-VLT-First
+ * (paper Section 4.2.1, the VLT equation, and Section 4.2.2, Algorithm 1).
+ *
+ * VLT of a request at time t_now:
+ *   rotary : alpha * ReLU(t_now - t_last - beta_B * S_B)
+ *   waiting:         ReLU(t_now - t_arr  - beta_F * S_F)
+ *   running:        -(t_now - t_run)
+ * Reading of the garbled sentence under the equation: the equation pairs S_B
+ * with rotary requests, which wait for their next token, so S_B is the
+ * time-between-tokens SLO, and S_F with waiting requests, so S_F is the
+ * time-to-first-token SLO.
+ *
+ * LVF, in the algorithm's order: contention check (if the free HBM blocks hold
+ * every waiting and rotary request, prioritise them all, first come first
+ * served, and preempt nobody); sort all requests by VLT, largest first; walk
+ * from the head and prioritise waiting / rotary requests with VLT >= 0 that
+ * still fit into B_HBM + B_xfer blocks; B_swap = B_xfer - B_left; walk from
+ * the tail and preempt running requests with VLT < 0 while B_swap > 0.
+ * Readings: ties in VLT are broken by ascending request id; only waiting and
+ * rotary requests can be prioritised (a running request whose VLT is exactly
+ * 0 is already in HBM); first come first served orders by the request's
+ * reference time (arrival, or last token), then id.
+ * ------------------------------------------------------------------------ */
+enum { OKV_RUNNING = 0, OKV_WAITING = 1, OKV_ROTARY = 2 };
+
+typedef struct {
+    double alpha, beta_b, beta_f; /* sensitivity weight and the two tolerance coefficients */
+    double slo_tbt, slo_ttft;     /* S_B and S_F, seconds */
+} okv_sched_params;
+
+typedef struct {
+    int32_t id;
+    int32_t state;  /* OKV_RUNNING / WAITING / ROTARY */
+    int32_t blocks; /* blk(r) */
+    int32_t pad;
+    double t_ref;   /* running: t_run; waiting: t_arr; rotary: t_last */
+} okv_sched_req;
+
+static double relu(double x) { return x > 0.0 ? x : 0.0; }
+
+double okv_sched_vlt(const okv_sched_params *p, const okv_sched_req *r, double t_now)
+{
+    if (r->state == OKV_ROTARY) return p->alpha * relu(t_now - r->t_ref - p->beta_b * p->slo_tbt);
+    if (r->state == OKV_WAITING) return relu(t_now - r->t_ref - p->beta_f * p->slo_ttft);
+    return -(t_now - r->t_ref);
+}
+
+/* preempt[] / prioritize[] receive request ids in the order they were chosen
+ * (room for n each).  *fcfs = 1 if the contention check short-circuited. */
+int okv_sched_lvf(const okv_sched_params *p, const okv_sched_req *reqs, int32_t n, double t_now,
+                  int32_t b_xfer, int32_t b_hbm, int32_t *preempt, int32_t *n_preempt,
+                  int32_t *prioritize, int32_t *n_prioritize, int32_t *fcfs)
+{
+    if (!p || n < 0 || (n > 0 && !reqs) || b_xfer < 0 || b_hbm < 0 || !n_preempt || !n_prioritize ||
+        (n > 0 && (!preempt || !prioritize)))
+        return OKV_EINVAL;
+    for (int32_t i = 0; i < n; i++)
+        if (reqs[i].state < OKV_RUNNING || reqs[i].state > OKV_ROTARY || reqs[i].blocks < 0)
+            return OKV_EINVAL;
+    *n_preempt = 0;
+    *n_prioritize = 0;
+    if (fcfs) *fcfs = 0;
+    int32_t *order = (int32_t *)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    double *vlt = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    for (int32_t i = 0; i < n; i++) {
+        order[i] = i;
+        vlt[i] = okv_sched_vlt(p, &reqs[i], t_now);
+    }
+    /* step 1: contention check */
+    int64_t need = 0;
+    for (int32_t i = 0; i < n; i++)
+        if (reqs[i].state != OKV_RUNNING) need += reqs[i].blocks;
+    if ((int64_t)b_hbm >= need) {
+        /* first come first served: insertion sort by (t_ref, id) */
+        for (int32_t a = 1; a < n; a++)
+            for (int32_t b = a; b > 0; b--) {
+                const okv_sched_req *x = &reqs[order[b - 1]], *y = &reqs[order[b]];
+                if (x->t_ref > y->t_ref || (x->t_ref == y->t_ref && x->id > y->id)) {
+                    int32_t t = order[b]; order[b] = order[b - 1]; order[b - 1] = t;
+                } else break;
+            }
+        for (int32_t i = 0; i < n; i++)
+            if (reqs[order[i]].state != OKV_RUNNING) prioritize[(*n_prioritize)++] = reqs[order[i]].id;
+        if (fcfs) *fcfs = 1;
+        free(order);
+        free(vlt);
+        return OKV_OK;
+    }
+    /* step 2: sort by VLT, largest first (ties: smaller id first) */
+    for (int32_t a = 1; a < n; a++)
+        for (int32_t b = a; b > 0; b--) {
+            int32_t x = order[b - 1], y = order[b];
+            if (vlt[x] < vlt[y] || (vlt[x] == vlt[y] && reqs[x].id > reqs[y].id)) {
+                order[b] = x; order[b - 1] = y;
+            } else break;
+        }
+    /* step 3: prioritise from the head */
+    int64_t left = (int64_t)b_hbm + b_xfer;
+    for (int32_t i = 0; i < n; i++) {
+        const okv_sched_req *r = &reqs[order[i]];
+        if (r->state != OKV_RUNNING && vlt[order[i]] >= 0.0 && r->blocks <= left) {
+            prioritize[(*n_prioritize)++] = r->id;
+            left -= r->blocks;
+        }
+    }
+    /* step 4: preempt from the tail */
+    int64_t swap = (int64_t)b_xfer - left;
+    for (int32_t i = n - 1; i >= 0; i--) {
+        const okv_sched_req *r = &reqs[order[i]];
+        if (r->state == OKV_RUNNING && vlt[order[i]] < 0.0 && swap > 0) {
+            preempt[(*n_preempt)++] = r->id;
+            swap -= r->blocks;
+        }
+    }
+    free(order);
+    free(vlt);
+    return OKV_OK;
+}

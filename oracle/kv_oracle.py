@@ -25,6 +25,18 @@ BLOCK_FIRST, LAYER_FIRST = 0, 1            # host pool layouts
 HBM_LAYER_FIRST, HBM_BLOCK_FIRST = 0, 1    # cache layouts
 
 
+class OkvSchedParams(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("alpha", "beta_b", "beta_f", "slo_tbt", "slo_ttft")]
+
+
+class OkvSchedReq(C.Structure):
+    _fields_ = [("id", C.c_int32), ("state", C.c_int32), ("blocks", C.c_int32), ("pad", C.c_int32),
+                ("t_ref", C.c_double)]
+
+
+RUNNING, WAITING, ROTARY = 0, 1, 2
+
+
 class OkvShape(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "head_dim", "block_size", "elem_bytes",
@@ -82,6 +94,11 @@ def lib() -> C.CDLL:
         L.okvt_blocks.argtypes = [C.c_void_p, C.c_int32, p32, p32, p32, C.c_int32, p32, p32]
         L.okvt_counts.restype = C.c_int
         L.okvt_counts.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+        L.okv_sched_vlt.restype = C.c_double
+        L.okv_sched_vlt.argtypes = [C.POINTER(OkvSchedParams), C.POINTER(OkvSchedReq), C.c_double]
+        L.okv_sched_lvf.restype = C.c_int
+        L.okv_sched_lvf.argtypes = [C.POINTER(OkvSchedParams), C.POINTER(OkvSchedReq), C.c_int32, C.c_double,
+                                    C.c_int32, C.c_int32, p32, p32, p32, p32, p32]
         L.okv_read_checksum.restype = C.c_int
         L.okv_read_checksum.argtypes = [ps, C.c_void_p, p32, C.c_int32, C.POINTER(C.c_uint64)]
         _lib = L
@@ -225,3 +242,22 @@ class Table:
 
     def __del__(self):
         self.close()
+
+
+def sched_vlt(params, req, t_now):
+    """params = (alpha, beta_b, beta_f, slo_tbt, slo_ttft); req = (id, state, blocks, t_ref)."""
+    p = OkvSchedParams(*params)
+    r = OkvSchedReq(req[0], req[1], req[2], 0, req[3])
+    return lib().okv_sched_vlt(C.byref(p), C.byref(r), t_now)
+
+
+def sched_lvf(params, reqs, t_now, b_xfer, b_hbm):
+    """(code, preempted ids, prioritised ids, fcfs flag)."""
+    p = OkvSchedParams(*params)
+    n = len(reqs)
+    arr = (OkvSchedReq * max(n, 1))(*[OkvSchedReq(r[0], r[1], r[2], 0, r[3]) for r in reqs])
+    pre, pri = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
+    npre, npri, fcfs = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = lib().okv_sched_lvf(C.byref(p), arr, n, t_now, b_xfer, b_hbm, pre, C.byref(npre), pri, C.byref(npri),
+                             C.byref(fcfs))
+    return rc, list(pre[:npre.value]), list(pri[:npri.value]), bool(fcfs.value)

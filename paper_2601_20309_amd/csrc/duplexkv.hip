@@ -211,12 +211,12 @@ struct MoveIds {
     const int32_t *out_ids, *out_slots, *in_ids, *in_slots;
 };
 
-template <int U, bool NT>
+template <int U>
 void launch_move_v(int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
 {
     dim3 g((unsigned)wgs), b((unsigned)lanes);
 #define DKV_LAUNCH(V) \
-    hipLaunchKernelGGL((dkv::kv_move_kernel<V, U, NT>), g, b, 0, s, p, d.out_ids, d.out_slots, d.in_ids, d.in_slots)
+    hipLaunchKernelGGL((dkv::kv_move_kernel<V, U>), g, b, 0, s, p, d.out_ids, d.out_slots, d.in_ids, d.in_slots)
     switch (vec) {
     case 16: DKV_LAUNCH(dkv::u32x4); break;
     case 8: DKV_LAUNCH(dkv::u32x2); break;
@@ -227,24 +227,13 @@ void launch_move_v(int vec, int wgs, int lanes, hipStream_t s, const MoveParams 
 #undef DKV_LAUNCH
 }
 
-bool g_nt = false;      // HBM-side non-temporal hint (measured: no gain on the link-bound path)
-
 void launch_move(int u, int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
 {
-    if (g_nt) {
-        switch (u) {
-        case 1: launch_move_v<1, true>(vec, wgs, lanes, s, p, d); break;
-        case 2: launch_move_v<2, true>(vec, wgs, lanes, s, p, d); break;
-        case 4: launch_move_v<4, true>(vec, wgs, lanes, s, p, d); break;
-        default: launch_move_v<8, true>(vec, wgs, lanes, s, p, d); break;
-        }
-    } else {
-        switch (u) {
-        case 1: launch_move_v<1, false>(vec, wgs, lanes, s, p, d); break;
-        case 2: launch_move_v<2, false>(vec, wgs, lanes, s, p, d); break;
-        case 4: launch_move_v<4, false>(vec, wgs, lanes, s, p, d); break;
-        default: launch_move_v<8, false>(vec, wgs, lanes, s, p, d); break;
-        }
+    switch (u) {
+    case 1: launch_move_v<1>(vec, wgs, lanes, s, p, d); break;
+    case 2: launch_move_v<2>(vec, wgs, lanes, s, p, d); break;
+    case 4: launch_move_v<4>(vec, wgs, lanes, s, p, d); break;
+    default: launch_move_v<8>(vec, wgs, lanes, s, p, d); break;
     }
 }
 
@@ -286,11 +275,12 @@ void pool_strides(const kv_engine *e, uint64_t &slot_stride, uint64_t &plane_str
     }
 }
 
-// tiles of one direction over `planes` planes; false if it does not fit 32 bits
+// tiles of one direction over `planes` planes; false if the count leaves no
+// headroom in 32 bits (the kernels step a tile index by the grid size)
 bool dir_tiles(uint32_t n, uint32_t planes, uint32_t tiles_per_seg, uint32_t &tiles)
 {
     const uint64_t t = (uint64_t)n * planes * tiles_per_seg;
-    if (t >= 0xFFFFFFFFull) return false;
+    if (t >= 0x7FFFFFFFull) return false;
     tiles = (uint32_t)t;
     return true;
 }
@@ -904,7 +894,6 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
         e->own_pool = true;
     }
     e->vec = pick_vec(e);
-    if (const char *nt = getenv("DUPLEXKV_NT")) g_nt = atoi(nt) != 0;
 
     if (stream_out) {
         e->s_out = (hipStream_t)stream_out;

@@ -53,21 +53,6 @@ struct MoveParams {
     DirDesc out, in;
 };
 
-// HBM-side accesses: every byte is touched once, so NT = true marks them
-// non-temporal (no reuse worth keeping in L2 / MALL).
-template <bool NT, typename V>
-__device__ __forceinline__ V ld_hbm(const V *p)
-{
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-template <bool NT, typename V>
-__device__ __forceinline__ void st_hbm(V *p, V v)
-{
-    if constexpr (NT) __builtin_nontemporal_store(v, p);
-    else *p = v;
-}
-
 // Tile t of direction d -> byte offsets (segment base + tile start) on both sides.
 __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d,
                                        const int32_t *__restrict__ ids,
@@ -130,7 +115,7 @@ __device__ __forceinline__ LaneTile<V> lane_tile(const MoveParams &p, const int3
 
 // Loads of one full tile: the far-side (host) loads first, they have the long
 // latency; then the HBM loads.  No lane predicate: all issue back to back.
-template <typename V, int U, bool NT, bool IN, bool OUT>
+template <typename V, int U, bool IN, bool OUT>
 __device__ __forceinline__ void tile_loads(const LaneTile<V> &a, uint32_t lanes, V (&vi)[U], V (&vo)[U])
 {
     if constexpr (IN) {
@@ -139,11 +124,11 @@ __device__ __forceinline__ void tile_loads(const LaneTile<V> &a, uint32_t lanes,
     }
     if constexpr (OUT) {
 #pragma unroll
-        for (int u = 0; u < U; u++) vo[u] = ld_hbm<NT>(a.src_o + u * lanes);
+        for (int u = 0; u < U; u++) vo[u] = a.src_o[u * lanes];
     }
 }
 
-template <typename V, int U, bool NT, bool IN, bool OUT>
+template <typename V, int U, bool IN, bool OUT>
 __device__ __forceinline__ void tile_stores(const LaneTile<V> &a, uint32_t lanes, const V (&vi)[U], const V (&vo)[U])
 {
     if constexpr (OUT) {
@@ -152,7 +137,7 @@ __device__ __forceinline__ void tile_stores(const LaneTile<V> &a, uint32_t lanes
     }
     if constexpr (IN) {
 #pragma unroll
-        for (int u = 0; u < U; u++) st_hbm<NT>(a.dst_i + u * lanes, vi[u]);
+        for (int u = 0; u < U; u++) a.dst_i[u * lanes] = vi[u];
     }
 }
 
@@ -161,7 +146,7 @@ __device__ __forceinline__ void tile_stores(const LaneTile<V> &a, uint32_t lanes
 // issued before the stores of the current one, so each lane keeps up to 2 * U
 // vectors per direction in flight and the link sees no gap between a
 // workgroup's tiles.  Returns the first tile index >= t_end of this workgroup.
-template <typename V, int U, bool NT, bool IN, bool OUT>
+template <typename V, int U, bool IN, bool OUT>
 __device__ __forceinline__ uint32_t run_full(const MoveParams &p, const int32_t *__restrict__ out_ids,
                                              const int32_t *__restrict__ out_slots,
                                              const int32_t *__restrict__ in_ids,
@@ -172,12 +157,12 @@ __device__ __forceinline__ uint32_t run_full(const MoveParams &p, const int32_t 
     const uint32_t tile_vecs = lanes * U;
     LaneTile<V> cur = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
     V ai[U], ao[U];
-    tile_loads<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+    tile_loads<V, U, IN, OUT>(cur, lanes, ai, ao);
     for (t += stride; t < t_end; t += stride) {
         const LaneTile<V> nxt = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
         V bi[U], bo[U];
-        tile_loads<V, U, NT, IN, OUT>(nxt, lanes, bi, bo);
-        tile_stores<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+        tile_loads<V, U, IN, OUT>(nxt, lanes, bi, bo);
+        tile_stores<V, U, IN, OUT>(cur, lanes, ai, ao);
         cur = nxt;
 #pragma unroll
         for (int u = 0; u < U; u++) {
@@ -185,13 +170,13 @@ __device__ __forceinline__ uint32_t run_full(const MoveParams &p, const int32_t 
             if constexpr (OUT) ao[u] = bo[u];
         }
     }
-    tile_stores<V, U, NT, IN, OUT>(cur, lanes, ai, ao);
+    tile_stores<V, U, IN, OUT>(cur, lanes, ai, ao);
     return t;
 }
 
 // One tile with per-lane range checks: only for shapes whose segments are not
 // a whole number of tiles.
-template <typename V, int U, bool NT>
+template <typename V, int U>
 __device__ __forceinline__ void tile_ragged(const MoveParams &p, const int32_t *__restrict__ out_ids,
                                             const int32_t *__restrict__ out_slots,
                                             const int32_t *__restrict__ in_ids,
@@ -209,13 +194,13 @@ __device__ __forceinline__ void tile_ragged(const MoveParams &p, const int32_t *
             if (v0 + u * lanes < p.vec_per_seg) vi[u] = a.src_i[u * lanes];
 #pragma unroll
         for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) st_hbm<NT>(a.dst_i + u * lanes, vi[u]);
+            if (v0 + u * lanes < p.vec_per_seg) a.dst_i[u * lanes] = vi[u];
     }
     if (do_out) {
         const LaneTile<V> a = lane_tile<V, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
 #pragma unroll
         for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) vo[u] = ld_hbm<NT>(a.src_o + u * lanes);
+            if (v0 + u * lanes < p.vec_per_seg) vo[u] = a.src_o[u * lanes];
 #pragma unroll
         for (int u = 0; u < U; u++)
             if (v0 + u * lanes < p.vec_per_seg) a.dst_o[u * lanes] = vo[u];
@@ -230,7 +215,7 @@ __device__ __forceinline__ void tile_ragged(const MoveParams &p, const int32_t *
 // list and tile t of the in list: while both lists last, every lane alternates
 // an out-vector with an in-vector, which locks the two link directions 1:1;
 // the longer list's remainder then runs alone.  Lists may be empty.
-template <typename V, int U, bool NT>
+template <typename V, int U>
 __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p,
                                                               const int32_t *__restrict__ out_ids,
                                                               const int32_t *__restrict__ out_slots,
@@ -242,14 +227,14 @@ __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p
     const uint32_t n_all = p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles;
     uint32_t t = blockIdx.x;
     if (!p.full_tiles) {
-        for (; t < n_all; t += stride) tile_ragged<V, U, NT>(p, out_ids, out_slots, in_ids, in_slots, t, lanes, tid);
+        for (; t < n_all; t += stride) tile_ragged<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lanes, tid);
         return;
     }
-    t = run_full<V, U, NT, true, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_both, stride, lanes, tid);
+    t = run_full<V, U, true, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_both, stride, lanes, tid);
     if (p.out.tiles > p.in.tiles)
-        run_full<V, U, NT, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
+        run_full<V, U, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
     else
-        run_full<V, U, NT, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
+        run_full<V, U, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
 }
 
 // Synthetic decode reader: streams every segment of the named blocks, plane by
