@@ -278,6 +278,48 @@ int kv_table_blocks(kv_table *table, int32_t req, int32_t *block_ids, int32_t *h
 
 int kv_table_get_counts(kv_table *table, kv_table_counts *out);
 
+/* ------------------------------------------------------------------------
+ * What rotates: Virtual Lag Time and Largest-VLT-First scheduling (paper
+ * Section 4.2.1, the VLT equation, and Section 4.2.2, Algorithm 1).  Host only.
+ *   VLT = alpha * ReLU(t_now - t_last - beta_b * slo_tbt)   rotary
+ *         ReLU(t_now - t_arr - beta_f * slo_ttft)           waiting
+ *         -(t_now - t_run)                                  running
+ * kv_sched_lvf: if the b_hbm free blocks hold every waiting and rotary
+ * request, all of them are prioritised first come first served (*fcfs = 1)
+ * and nobody is preempted.  Otherwise requests are sorted by VLT, largest
+ * first (ties: smaller id); waiting / rotary requests with VLT >= 0 are
+ * prioritised from the head while they fit into b_hbm + b_xfer blocks; then
+ * running requests with VLT < 0 are preempted from the tail while
+ * b_swap = b_xfer - blocks left is positive.  preempt[] and prioritize[]
+ * (room for n ids each) receive request ids in the order chosen; they are
+ * what kv_table_rotate() takes.
+ * ------------------------------------------------------------------------ */
+#define KV_REQ_RUNNING 0
+#define KV_REQ_WAITING 1
+#define KV_REQ_ROTARY  2
+
+typedef struct {
+    double alpha;    /* sensitivity weight of rotary (between-token) lag, >= 0 */
+    double beta_b;   /* tolerance coefficient on slo_tbt */
+    double beta_f;   /* tolerance coefficient on slo_ttft */
+    double slo_tbt;  /* S_B: time-between-tokens SLO, seconds */
+    double slo_ttft; /* S_F: time-to-first-token SLO, seconds */
+} kv_sched_params;
+
+typedef struct {
+    int32_t id;
+    int32_t state;   /* KV_REQ_* */
+    int32_t blocks;  /* blk(r): KV blocks the request holds or needs */
+    int32_t pad;
+    double t_ref;    /* running: t_run; waiting: t_arr; rotary: t_last (seconds) */
+} kv_sched_req;
+
+double kv_sched_vlt(const kv_sched_params *params, const kv_sched_req *req, double t_now);
+
+int kv_sched_lvf(const kv_sched_params *params, const kv_sched_req *reqs, int32_t n, double t_now,
+                 int32_t b_xfer, int32_t b_hbm, int32_t *preempt, int32_t *n_preempt, int32_t *prioritize,
+                 int32_t *n_prioritize, int32_t *fcfs);
+
 const char *kv_strerror(int code);
 
 #ifdef __cplusplus

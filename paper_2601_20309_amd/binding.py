@@ -29,7 +29,9 @@ EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", 
            "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
            "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
            "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate",
-           "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_strerror"]
+           "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_sched_vlt", "kv_sched_lvf",
+           "kv_strerror"]
+KV_REQ_RUNNING, KV_REQ_WAITING, KV_REQ_ROTARY = 0, 1, 2
 
 
 class kv_config(C.Structure):
@@ -48,6 +50,15 @@ class kv_stats(C.Structure):
 class kv_table_counts(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("free_hbm_blocks", "free_host_slots", "copied_eager",
                                          "copied_preempt", "dropped_synced", "swapped_in")]
+
+
+class kv_sched_params(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("alpha", "beta_b", "beta_f", "slo_tbt", "slo_ttft")]
+
+
+class kv_sched_req(C.Structure):
+    _fields_ = [("id", C.c_int32), ("state", C.c_int32), ("blocks", C.c_int32), ("pad", C.c_int32),
+                ("t_ref", C.c_double)]
 
 
 class KVError(RuntimeError):
@@ -106,6 +117,11 @@ def _load() -> C.CDLL:
     L.kv_table_blocks.argtypes = [C.c_void_p, C.c_int32, p32, p32, p32, C.c_int32, p32, p32]
     L.kv_table_get_counts.restype = C.c_int
     L.kv_table_get_counts.argtypes = [C.c_void_p, C.POINTER(kv_table_counts)]
+    L.kv_sched_vlt.restype = C.c_double
+    L.kv_sched_vlt.argtypes = [C.POINTER(kv_sched_params), C.POINTER(kv_sched_req), C.c_double]
+    L.kv_sched_lvf.restype = C.c_int
+    L.kv_sched_lvf.argtypes = [C.POINTER(kv_sched_params), C.POINTER(kv_sched_req), C.c_int32, C.c_double,
+                               C.c_int32, C.c_int32, p32, p32, p32, p32, p32]
     L.kv_strerror.restype = C.c_char_p
     L.kv_strerror.argtypes = [C.c_int]
     return L
@@ -156,6 +172,25 @@ def kv_probe_link(nbytes: int, reps: int = 5) -> dict:
     if rc != KV_OK:
         raise KVError(rc, "kv_probe_link")
     return dict(d2h=v[0].value, h2d=v[1].value, d2h_duplex=v[2].value, h2d_duplex=v[3].value)
+
+
+def kv_sched_vlt(params, req, t_now: float) -> float:
+    """params = (alpha, beta_b, beta_f, slo_tbt, slo_ttft); req = (id, state, blocks, t_ref)."""
+    p = kv_sched_params(*params)
+    r = kv_sched_req(req[0], req[1], req[2], 0, req[3])
+    return lib.kv_sched_vlt(C.byref(p), C.byref(r), t_now)
+
+
+def kv_sched_lvf(params, reqs, t_now: float, b_xfer: int, b_hbm: int):
+    """(code, preempted ids, prioritised ids, fcfs flag)."""
+    p = kv_sched_params(*params)
+    n = len(reqs)
+    arr = (kv_sched_req * max(n, 1))(*[kv_sched_req(r[0], r[1], r[2], 0, r[3]) for r in reqs])
+    pre, pri = (C.c_int32 * max(n, 1))(), (C.c_int32 * max(n, 1))()
+    npre, npri, fcfs = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = lib.kv_sched_lvf(C.byref(p), arr, n, t_now, b_xfer, b_hbm, pre, C.byref(npre), pri, C.byref(npri),
+                          C.byref(fcfs))
+    return rc, list(pre[:npre.value]), list(pri[:npri.value]), bool(fcfs.value)
 
 
 class Engine:
