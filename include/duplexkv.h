@@ -187,8 +187,8 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d,
  * execution with rotation").  Streams every segment of the named HBM blocks,
  * layer by layer, `passes` times (1..256), on a stream of the engine's own so
  * that it overlaps kv_rotate, and reduces what it read to the sum modulo 2^64
- * of all little-endian 32-bit words (a block named twice counts twice).  Read
- * only.  Needs segments that are multiples of 16 bytes (KV_EUNSUP otherwise).
+ * of all little-endian 32-bit words (a block named twice counts twice; n may
+ * be up to twice n_hbm_blocks).  Read only.  Needs segments that are multiples of 16 bytes (KV_EUNSUP otherwise).
  * max_wgs caps its persistent workgroups (0 = engine picks).  One reader at a time:
  * kv_reader_wait() must come before the next kv_reader_start().
  */

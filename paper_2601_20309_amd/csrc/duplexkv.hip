@@ -170,7 +170,7 @@ struct kv_engine {
 
     // synthetic decode reader
     hipStream_t s_read = nullptr;
-    int32_t *read_ids = nullptr;               // device, n_hbm_blocks ints
+    int32_t *read_ids = nullptr;               // device, 2 * n_hbm_blocks ints
     int32_t *read_ids_host = nullptr;          // pinned
     unsigned long long *read_acc = nullptr;    // device: [0] sum, then one 32-bit tile counter per pass
     unsigned long long *read_acc_host = nullptr;  // pinned
@@ -1075,10 +1075,10 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
     if (e->sticky != KV_OK) return e->sticky;
     if (e->read_passes != 0) return KV_EINVAL;  // previous reader not waited for
     if (out_of_range(ids, n, e->cfg.n_hbm_blocks)) return KV_ERANGE;
-    if (n > e->cfg.n_hbm_blocks) return KV_EINVAL;
+    if ((int64_t)n > 2 * (int64_t)e->cfg.n_hbm_blocks) return KV_EINVAL;
     if (e->seg % 16 != 0 || ((uintptr_t)e->hbm & 15u) != 0) return KV_EUNSUP;
     if (!e->s_read) {
-        const size_t idb = (size_t)e->cfg.n_hbm_blocks * sizeof(int32_t);
+        const size_t idb = 2 * (size_t)e->cfg.n_hbm_blocks * sizeof(int32_t);
         if (hipMalloc((void **)&e->read_ids, idb) != hipSuccess ||
             hipHostMalloc((void **)&e->read_ids_host, idb, hipHostMallocDefault) != hipSuccess ||
             hipMalloc((void **)&e->read_acc, sizeof(unsigned long long) + 256 * sizeof(unsigned int)) != hipSuccess ||

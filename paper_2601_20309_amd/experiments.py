@@ -7,6 +7,7 @@
   python -m paper_2601_20309_amd.experiments eager         # a preemption with and without eager block rotation
   python -m paper_2601_20309_amd.experiments layouts       # layer-first against block-first cache layout
   python -m paper_2601_20309_amd.experiments linksweep     # bandwidth against segment size, copies and kernels
+  python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -418,8 +419,174 @@ def eager():
         eng.kv_destroy()
 
 
+def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slots=16384):
+    """Cross-iteration pipeline (Section 4.3.2) with synthetic traffic: while the
+    GPU "executes" iteration t (the decode reader streams the KV of the running
+    batch plus a weights-sized read), LVF (Algorithm 1) picks what rotates for
+    iteration t+1 and the block table moves it, eager copies included.  Reports
+    how often the rotation outlasted the execution (a stall) and the time split,
+    the quantities of the paper's Section 5.4 stall paragraph."""
+    shape = W.SHAPES["llama3_8b"]                 # blocks of 16 tokens; a small cache so that requests must rotate
+    shape = W.KVShape(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
+                      n_hbm_blocks=hbm_blocks, n_host_slots=host_slots)
+    P = shape.block_size
+    cache = _cache(shape)
+    eng = B.Engine(B.make_config(shape, max_copy_wgs=32), cache.data_ptr())   # co-running: small footprint
+    tab = B.Table(eng, 4096)
+    blk = B.kv_block_bytes(eng.cfg)
+    params = (3.0, 0.0, 0.5, 0.1, 5.0)            # alpha, beta_B, beta_F, S_B = 100 ms, S_F = 5 s (Section 5.1)
+    rng = np.random.default_rng(seed)
+    # a 16 GiB read per iteration stands for the model weights (Llama-3-8B in bf16)
+    # (the batch's own KV lies inside it: the reader takes at most 2 x hbm_blocks ids)
+    weights_ids = (np.arange(0, min(8192, 2 * hbm_blocks), dtype=np.int64) % hbm_blocks).astype(np.int32)
+    # link budget per iteration: what 80 % of the measured both-ways rate moves during one
+    # execution, re-derived from the running average of the execution time
+    fixed_budget = b_xfer
+    b_xfer = fixed_budget if fixed_budget is not None else int(0.8 * 48e9 * 3e-3 / blk)
+    arrivals = np.cumsum(rng.exponential(1.0 / rps, size=int(rps * seconds * 1.2) + 8))
+    prompts = np.clip(np.rint(rng.lognormal(np.log(700), 0.9, size=arrivals.size)), 16, 8192).astype(int)
+    outputs = np.clip(np.rint(rng.lognormal(np.log(200), 0.8, size=arrivals.size)), 4, 2048).astype(int)
+    state, t_ref, length, target, ids_of = {}, {}, {}, {}, {}
+    ttft, tbt, first_done = [], [], set()
+    free_ids = list(range(4095, -1, -1))
+    now, next_arrival, it = 0.0, 0, 0
+    n_stall, t_sched, t_xfer, t_exec, moved_blocks = 0, [], [], [], 0
+    arrive_time = {}
+    while now < seconds:
+        while next_arrival < arrivals.size and arrivals[next_arrival] <= now and free_ids:
+            r = free_ids.pop()
+            state[r], t_ref[r] = B.KV_REQ_WAITING, float(arrivals[next_arrival])
+            arrive_time[r] = float(arrivals[next_arrival])
+            length[r], target[r] = int(prompts[next_arrival]), int(prompts[next_arrival] + outputs[next_arrival])
+            next_arrival += 1
+        # ---- host: schedule iteration t+1 -------------------------------------------------------
+        h0 = time.perf_counter()
+        reqs = [(r, state[r], -(-length[r] // P), t_ref[r]) for r in state]
+        free_hbm = tab.kv_table_get_counts()["free_hbm_blocks"]
+        rc, pre, pri, fcfs = B.kv_sched_lvf(params, reqs, now, b_xfer, free_hbm)
+        assert rc == 0
+        # leave room for the tokens the running batch is about to append
+        running_after = [r for r in state if state[r] == B.KV_REQ_RUNNING and r not in pre]
+        headroom = len(running_after) + 8
+        admit, resume, room = [], [], free_hbm + sum(-(-length[r] // P) for r in pre) - headroom
+        swap_in_left = b_xfer                     # the budget bounds what one iteration swaps (Section 4.2.2)
+        for r in pri:
+            need = -(-length[r] // P) + 1
+            if need > room:
+                continue
+            if state[r] == B.KV_REQ_ROTARY:
+                if need - 1 > swap_in_left:
+                    continue
+                swap_in_left -= need - 1
+                resume.append(r)
+            else:
+                admit.append(r)
+            room -= need
+        rc = tab.kv_table_rotate(pre, resume)
+        if rc == B.KV_ENOSPC:                     # copied-out blocks are not reusable within the call
+            resume = []
+            rc = tab.kv_table_rotate(pre, [])
+        assert rc == 0, B.kv_strerror(rc)
+        c0 = tab.kv_table_get_counts()
+        for r in admit:
+            rc, new = tab.kv_table_append(r, length[r])
+            if rc != 0:
+                continue
+            ids_of[r] = list(new)
+            state[r], t_ref[r] = B.KV_REQ_RUNNING, now
+        for r in pre:
+            state[r], t_ref[r] = B.KV_REQ_ROTARY, t_ref.get(("last", r), now)
+        for r in resume:
+            state[r], t_ref[r] = B.KV_REQ_RUNNING, now
+            ids_of[r] = tab.kv_table_blocks(r)["ids"]
+        spent = sum(-(-length[r] // P) for r in resume) + sum(1 for _ in pre)
+        rc, n_eager = tab.kv_table_eager(max(0, b_xfer - spent))
+        assert rc == 0
+        t_sched.append((time.perf_counter() - h0) * 1e3)
+        # ---- GPU: execute iteration t while the rotation runs -------------------------------------
+        batch = [r for r in state if state[r] == B.KV_REQ_RUNNING and r not in resume and r not in admit]
+        read_ids = weights_ids
+        x0 = time.perf_counter()
+        assert eng.kv_reader_start(read_ids, 1) == 0
+        assert eng.kv_wait() == 0
+        xfer_ms = (time.perf_counter() - x0) * 1e3
+        rc, _, pm = eng.kv_reader_wait()
+        assert rc == 0
+        exec_ms = pm[0]
+        st = eng.kv_last_stats()
+        moved = (st["bytes_out"] + st["bytes_in"]) // blk
+        moved_blocks += moved
+        if moved:
+            t_xfer.append(xfer_ms)
+            n_stall += xfer_ms > exec_ms
+        t_exec.append(exec_ms)
+        if fixed_budget is None:
+            b_xfer = max(8, int(0.8 * 48e9 * float(np.mean(t_exec[-32:])) * 1e-3 / blk))
+        now += max(exec_ms, xfer_ms if moved else 0.0) * 1e-3 + t_sched[-1] * 1e-3 * 0  # scheduling overlaps execution
+        it += 1
+        # ---- every request of the batch (and every admitted prompt) yields one token ----------------
+        for r in batch + admit:
+            if state.get(r) != B.KV_REQ_RUNNING:
+                continue
+            if r not in first_done:
+                first_done.add(r)
+                ttft.append(now - arrive_time[r])
+            else:
+                tbt.append(now - t_ref[("last", r)])
+            t_ref[("last", r)] = now
+            length[r] += 1
+            if length[r] >= target[r]:
+                assert eng.kv_wait() == 0
+                assert tab.kv_table_finish(r) == 0
+                for d in (state, length, target, ids_of):
+                    d.pop(r, None)
+                t_ref.pop(r, None); t_ref.pop(("last", r), None)
+                first_done.discard(r)
+                free_ids.append(r)
+                continue
+            rc, new = tab.kv_table_append(r, 1)
+            if rc == 0:
+                ids_of[r].extend(new)
+            else:
+                length[r] -= 1                    # cache full: the token waits for the next iteration
+    # every synced block must still equal its DRAM copy
+    assert eng.kv_wait() == 0
+    pool = eng.host_pool_array().view(np.uint16).reshape((shape.n_host_slots,) + shape.block_dims())
+    checked = 0
+    for r in [r for r in state if state[r] == B.KV_REQ_RUNNING][:24]:
+        b = tab.kv_table_blocks(r)
+        if b is None:
+            continue
+        sel = [i for i, s_ in enumerate(b["states"]) if s_ == B.KV_BLOCK_SYNCED][:8]
+        if not sel:
+            continue
+        hb = cache.view(torch.int16)[:, :, torch.tensor([b["ids"][i] for i in sel], device="cuda")].cpu().numpy()
+        assert np.array_equal(hb.view(np.uint16).transpose(2, 0, 1, 3, 4, 5), pool[[b["slots"][i] for i in sel]])
+        checked += len(sel)
+    c = tab.kv_table_get_counts()
+    q = lambda a, p_: float(np.percentile(a, p_)) if len(a) else float("nan")
+    print(f"\nsynthetic serving, {rps:g} requests/s for {seconds:g} s of virtual time, B_xfer = {b_xfer} blocks "
+          f"({b_xfer * blk / 2**20:.0f} MiB) per iteration{'' if fixed_budget is not None else ' (0.8 x link rate x execution time)'}, "
+          f"HBM cache {shape.n_hbm_blocks} blocks, {len(state)} requests still in flight\n")
+    print("| iterations | with a rotation | stalled (rotation outlasted execution) | schedule ms avg | transfer ms avg | "
+          "execution ms avg | blocks moved | eager copies | copied at preemption | dropped without copy | swapped in |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
+    print(f"| {it} | {len(t_xfer)} | {n_stall} ({100.0 * n_stall / max(it, 1):.2f} % of iterations) | {np.mean(t_sched):.2f} | "
+          f"{np.mean(t_xfer) if t_xfer else 0:.2f} | {np.mean(t_exec):.2f} | {moved_blocks} | {c['copied_eager']} | "
+          f"{c['copied_preempt']} | {c['dropped_synced']} | {c['swapped_in']} |")
+    print(f"\nTTFT p50 / p99: {q(ttft, 50):.3f} / {q(ttft, 99):.3f} s over {len(ttft)} requests; "
+          f"TBT p50 / p99: {q(tbt, 50) * 1e3:.1f} / {q(tbt, 99) * 1e3:.1f} ms over {len(tbt)} tokens; "
+          f"{checked} synced blocks re-checked against their DRAM copies")
+    tab.kv_table_destroy()
+    eng.kv_destroy()
+    return dict(iterations=it, stalled=n_stall, counts=c, checked=checked, in_flight=len(state))
+
+
 if __name__ == "__main__":
     what = sys.argv[1] if len(sys.argv) > 1 else "configs"
+    if what == "serve" and len(sys.argv) > 2:
+        serve(rps=float(sys.argv[2]), seconds=float(sys.argv[3]) if len(sys.argv) > 3 else 20.0)
+        sys.exit(0)
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
-     "linksweep": linksweep}[what]()
+     "linksweep": linksweep, "serve": serve}[what]()
