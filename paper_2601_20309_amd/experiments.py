@@ -8,6 +8,7 @@
   python -m paper_2601_20309_amd.experiments layouts       # layer-first against block-first cache layout
   python -m paper_2601_20309_amd.experiments linksweep     # bandwidth against segment size, copies and kernels
   python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
+  python -m paper_2601_20309_amd.experiments sizes         # rotation rate against rotation size
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -232,6 +233,26 @@ def linksweep():
         print("| " + " | ".join(row) + " |", flush=True)
         del cache
         torch.cuda.empty_cache()
+
+
+def sizes():
+    """Rotation rate against rotation size: n scattered blocks out while n come in
+    (Llama-3-8B shape, 2 MiB blocks), one kv_rotate + kv_wait per step."""
+    shape = W.SHAPES["llama3_8b"]
+    cache = _cache(shape)
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    print("\n| blocks each way | MiB each way | step us | out+in GB/s |")
+    print("|---|---|---|---|")
+    for n in [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]:
+        rot = W.simple_rotation(shape, n, n, seed=n)
+        calls = _rot_calls(eng, rot)
+
+        def fn(i):
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+        ms, _, _ = _time_calls(eng, fn, 20 if n <= 128 else 6, warm=4)
+        print(f"| {n} | {n * blk >> 20} | {ms * 1e3:.1f} | {2 * n * blk / ms / 1e6:.2f} |", flush=True)
+    eng.kv_destroy()
 
 
 def configs():
@@ -589,4 +610,5 @@ if __name__ == "__main__":
         sys.exit(0)
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
-     "linksweep": linksweep, "serve": serve}[what]()
+     "linksweep": linksweep, "serve": serve,
+     "sizes": sizes}[what]()
