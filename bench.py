@@ -225,6 +225,21 @@ def main():
             "hbm_frac": round((bytes_out + bytes_in) / (kern_ms * 1e6) / HBM_PEAK_GBPS, 5),
         },
     }
+    # the hot path's HBM-bound kernel (the decode reader that runs beside rotations), measured
+    # live on its own stream with HIP events: every block of the cache, 6 passes
+    all_ids = np.arange(shape.n_hbm_blocks, dtype=np.int32)
+    assert eng.kv_reader_start(all_ids, 6) == 0
+    rc, _, pass_ms = eng.kv_reader_wait()
+    assert rc == 0
+    rd_ms = float(np.median(pass_ms[1:]))
+    rd_bytes = shape.n_hbm_blocks * blk
+    res["roofline_hbm_kernel"] = {
+        "bound": "hbm", "kernel": "kv_reader_kernel (synthetic decode reader, whole cache per launch)",
+        "achieved": round(rd_bytes / (rd_ms * 1e6), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(rd_bytes / (rd_ms * 1e6) / HBM_PEAK_GBPS, 4), "kernel_ms": round(rd_ms, 4),
+        # FETCH_SIZE x 2.000 of profiles/kv_reader_kernel_interference_shape.txt: 1.0023 x algorithmic
+        "traffic": int(rd_bytes * 1.0023), "traffic_algorithmic": rd_bytes,
+    }
     eng.kv_destroy()
     del cache
     torch.cuda.empty_cache()

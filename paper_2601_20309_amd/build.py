@@ -7,8 +7,10 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "duplexkv.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "kv_kernels.hpp"), os.path.join(ROOT, "include", "duplexkv.h")]
+CSRC = os.path.join(HERE, "csrc")
+SRCS = [os.path.join(CSRC, n) for n in ("duplexkv.hip", "kv_table.cpp", "kv_sched.cpp")]
+DEPS = SRCS + [os.path.join(CSRC, "kv_kernels.hpp"), os.path.join(CSRC, "kv_engine.hpp"),
+               os.path.join(ROOT, "include", "duplexkv.h")]
 LIB = os.path.join(HERE, "libduplexkv.so")
 
 HIPCC_FLAGS = [
@@ -29,7 +31,7 @@ def stale() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if force or stale():
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-o", LIB, SRC]
+        cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-o", LIB] + SRCS
         if verbose:
             print(" ".join(cmd))
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -22,13 +22,12 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <functional>
 #include <new>
-#include <queue>
 #include <vector>
 
-#include "../../include/duplexkv.h"
+#include "kv_engine.hpp"
 #include "kv_kernels.hpp"
+
 
 namespace {
 
@@ -67,22 +66,9 @@ bool config_ok(const kv_config *c)
 }
 
 // ---- admission (host only) ------------------------------------------------
-// mark[] holds (epoch << 2) | bits, bits: 1 = named by the out list, 2 = by the in list.
-struct Marks {
-    std::vector<uint32_t> blk, slot;
-    uint32_t epoch = 0;
-    void reset(size_t nb, size_t ns) { blk.assign(nb, 0); slot.assign(ns, 0); epoch = 0; }
-    void next()
-    {
-        if (++epoch >= (1u << 30)) {
-            std::fill(blk.begin(), blk.end(), 0u);
-            std::fill(slot.begin(), slot.end(), 0u);
-            epoch = 1;
-        }
-    }
-};
-
-bool list_bad(const int32_t *p, int32_t n) { return n < 0 || (n > 0 && !p); }
+using dkv::Marks;
+using dkv::kRing;
+using dkv::list_bad;
 
 bool out_of_range(const int32_t *p, int32_t n, int32_t lim)
 {
@@ -122,61 +108,8 @@ int admit(const kv_config *c, Marks &mk, const int32_t *oi, const int32_t *os, i
     return KV_OK;
 }
 
-constexpr int kRing = 8;  // descriptor sets that may be in flight
-
 }  // namespace
 
-struct kv_engine {
-    kv_config cfg;
-    int device = 0;
-    uint64_t seg = 0, block_bytes = 0, cache_bytes = 0, pool_bytes = 0;
-    uint32_t n_planes = 0;
-    int vec = 1;  // bytes per lane access
-    uint8_t *hbm = nullptr;
-    uint8_t *pool = nullptr;
-    bool own_pool = false;
-    hipStream_t s_out = nullptr, s_in = nullptr;
-    bool own_streams = false;
-    int n_cus = 0;
-
-    // descriptor ring: per set [out_ids | out_slots | in_ids | in_slots]
-    int32_t *desc_host = nullptr, *desc_dev = nullptr;
-    size_t desc_cap = 0;  // ints per set
-    // ring_out[k] / ring_in[k] are recorded after the last work that reads set k
-    // on each stream; they double as the end-of-work timestamps for the stats
-    hipEvent_t ring_out[kRing] = {}, ring_in[kRing] = {};
-    bool ring_out_rec[kRing] = {}, ring_in_rec[kRing] = {};
-    int ring_cur = 0;
-
-    Marks marks;
-    std::vector<std::pair<int32_t, int32_t>> sort_tmp;  // (slot, id)
-
-    // stats
-    hipEvent_t ev_o0 = nullptr, ev_o1 = nullptr, ev_i0 = nullptr, ev_i1 = nullptr, ev_join = nullptr;
-    hipEvent_t b_o0 = nullptr, b_o1 = nullptr, b_i0 = nullptr, b_i1 = nullptr;  // this batch's first start / last end
-    bool batch_open = false;
-    bool out_pending = false, in_pending = false;  // work enqueued since the last kv_wait
-    bool in_dirty = false;                         // stream_in holds work stream_out has not joined
-    bool in_after_out = false;                     // block table in use: in-only work waits for earlier out work
-    double t0 = 0;
-    kv_stats acc{}, last{};
-    int sticky = KV_OK;
-
-    // staging for SDMA_STAGED: one buffer per direction, chunk_cap bytes each.
-    // A direction's pack / copy / unpack all run in order on that direction's
-    // stream, so a buffer is never reused before its last reader is done.
-    uint8_t *stage_out = nullptr, *stage_in = nullptr;
-    uint64_t chunk_cap = 0;
-
-    // synthetic decode reader
-    hipStream_t s_read = nullptr;
-    int32_t *read_ids = nullptr;               // device, 2 * n_hbm_blocks ints
-    int32_t *read_ids_host = nullptr;          // pinned
-    unsigned long long *read_acc = nullptr;    // device: [0] sum, then one 32-bit tile counter per pass
-    unsigned long long *read_acc_host = nullptr;  // pinned
-    std::vector<hipEvent_t> read_ev;           // passes + 1 timestamps
-    int32_t read_passes = 0;
-};
 
 namespace {
 
@@ -1148,312 +1081,6 @@ int kv_reader_wait(kv_engine *e, uint64_t *checksum, double *ms_per_pass)
         }
     }
     e->read_passes = 0;
-    return KV_OK;
-}
-
-// ---- block table with eager rotation ------------------------------------------
-}  // extern "C"
-
-namespace {
-
-struct TableReq {
-    bool used = false, resident = false;
-    int32_t len = 0;
-    std::vector<int32_t> hbm, slot, state;
-};
-
-// ids that are free, lowest first
-using FreeIds = std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>>;
-
-}  // namespace
-
-struct kv_table {
-    kv_engine *e = nullptr;
-    int32_t max_req = 0;
-    std::vector<TableReq> req;
-    FreeIds free_hbm, free_slot;
-    kv_table_counts cnt{};
-    std::vector<int32_t> oi, os, ii, is, held, seen;
-};
-
-extern "C" {
-
-int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
-{
-    if (!out) return KV_EINVAL;
-    *out = nullptr;
-    if (!e || max_requests <= 0) return KV_EINVAL;
-    if (e->cfg.path == KV_PATH_SDMA_STAGED || e->cfg.path == KV_PATH_NAIVE || e->cfg.path == KV_PATH_DMA_BLOCKS)
-        return KV_EUNSUP;
-    kv_table *t = new (std::nothrow) kv_table;
-    if (!t) return KV_ENOMEM;
-    t->e = e;
-    t->max_req = max_requests;
-    t->req.resize((size_t)max_requests);
-    for (int32_t i = 0; i < e->cfg.n_hbm_blocks; i++) t->free_hbm.push(i);
-    for (int32_t i = 0; i < e->cfg.n_host_slots; i++) t->free_slot.push(i);
-    t->seen.assign((size_t)max_requests, 0);
-    e->in_after_out = true;
-    *out = t;
-    return KV_OK;
-}
-
-int kv_table_destroy(kv_table *t)
-{
-    if (!t) return KV_EINVAL;
-    t->e->in_after_out = false;
-    delete t;
-    return KV_OK;
-}
-
-int kv_table_append(kv_table *t, int32_t rq, int32_t n_tokens, int32_t *new_ids, int32_t cap, int32_t *n_new)
-{
-    if (!t || rq < 0 || rq >= t->max_req || n_tokens < 0) return KV_EINVAL;
-    TableReq &r = t->req[(size_t)rq];
-    if (r.used && !r.resident) return KV_EINVAL;
-    const int32_t P = t->e->cfg.block_size;
-    const int32_t old_len = r.used ? r.len : 0, old_n = r.used ? (int32_t)r.hbm.size() : 0;
-    const int64_t new_len = (int64_t)old_len + n_tokens;
-    const int64_t need = (new_len + P - 1) / P - old_n;
-    if (need > (int64_t)t->free_hbm.size()) return KV_ENOSPC;
-    if (new_ids && need > cap) return KV_EINVAL;
-    if (!r.used) {
-        r = TableReq{};
-        r.used = r.resident = true;
-    }
-    if (n_tokens > 0 && old_len % P != 0) r.state[(size_t)old_n - 1] = KV_BLOCK_DIRTY;
-    for (int64_t k = 0; k < need; k++) {
-        const int32_t b = t->free_hbm.top();
-        t->free_hbm.pop();
-        r.hbm.push_back(b);
-        r.slot.push_back(-1);
-        r.state.push_back(KV_BLOCK_DIRTY);
-        if (new_ids) new_ids[k] = b;
-    }
-    r.len = (int32_t)new_len;
-    for (size_t i = 0; i < r.hbm.size(); i++)
-        if ((int64_t)(i + 1) * P <= r.len && r.state[i] == KV_BLOCK_DIRTY) r.state[i] = KV_BLOCK_FULL;
-    if (n_new) *n_new = (int32_t)need;
-    return KV_OK;
-}
-
-int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
-{
-    if (!t || budget < 0) return KV_EINVAL;
-    t->oi.clear();
-    t->os.clear();
-    std::vector<std::pair<int32_t, size_t>> picked;  // (request, block index)
-    std::vector<int32_t> fresh;                      // slots taken for this call
-    for (int32_t q = 0; q < t->max_req && (int32_t)t->oi.size() < budget; q++) {
-        TableReq &r = t->req[(size_t)q];
-        if (!r.used || !r.resident) continue;
-        for (size_t i = 0; i < r.hbm.size() && (int32_t)t->oi.size() < budget; i++) {
-            if (r.state[i] != KV_BLOCK_FULL) continue;
-            int32_t sl = r.slot[i];
-            if (sl < 0) {
-                if (t->free_slot.empty()) goto issue;
-                sl = t->free_slot.top();
-                t->free_slot.pop();
-                fresh.push_back(sl);
-            }
-            t->oi.push_back(r.hbm[i]);
-            t->os.push_back(sl);
-            picked.push_back({q, i});
-        }
-    }
-issue:
-    if (!t->oi.empty()) {
-        int rc = kv_swap_out(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size());
-        if (rc != KV_OK) {
-            for (int32_t sl : fresh) t->free_slot.push(sl);
-            return rc;
-        }
-        for (size_t k = 0; k < picked.size(); k++) {
-            TableReq &r = t->req[(size_t)picked[k].first];
-            r.slot[picked[k].second] = t->os[k];
-            r.state[picked[k].second] = KV_BLOCK_SYNCED;
-        }
-    }
-    t->cnt.copied_eager += (int64_t)t->oi.size();
-    if (n_done) *n_done = (int32_t)t->oi.size();
-    return KV_OK;
-}
-
-int kv_table_rotate(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res)
-{
-    if (!t || list_bad(pre, n_pre) || list_bad(res, n_res)) return KV_EINVAL;
-    // who is named, and is each one in the right place
-    int rc = KV_OK;
-    for (int32_t i = 0; i < n_pre && rc == KV_OK; i++) {
-        if (pre[i] < 0 || pre[i] >= t->max_req) { rc = KV_EINVAL; break; }
-        TableReq &r = t->req[(size_t)pre[i]];
-        if (!r.used || !r.resident || t->seen[(size_t)pre[i]]) rc = KV_EINVAL;
-        else t->seen[(size_t)pre[i]] = 1;
-    }
-    for (int32_t i = 0; i < n_res && rc == KV_OK; i++) {
-        if (res[i] < 0 || res[i] >= t->max_req) { rc = KV_EINVAL; break; }
-        TableReq &r = t->req[(size_t)res[i]];
-        if (!r.used || r.resident || t->seen[(size_t)res[i]]) rc = KV_EINVAL;
-        else t->seen[(size_t)res[i]] = 1;
-    }
-    for (int32_t i = 0; i < n_pre; i++)
-        if (pre[i] >= 0 && pre[i] < t->max_req) t->seen[(size_t)pre[i]] = 0;
-    for (int32_t i = 0; i < n_res; i++)
-        if (res[i] >= 0 && res[i] < t->max_req) t->seen[(size_t)res[i]] = 0;
-    if (rc != KV_OK) return rc;
-    // room, before anything changes
-    int64_t need_slots = 0, drop = 0, need_hbm = 0;
-    for (int32_t i = 0; i < n_pre; i++) {
-        const TableReq &r = t->req[(size_t)pre[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            if (r.state[b] == KV_BLOCK_SYNCED) drop++;
-            else if (r.slot[b] < 0) need_slots++;
-        }
-    }
-    for (int32_t i = 0; i < n_res; i++) need_hbm += (int64_t)t->req[(size_t)res[i]].hbm.size();
-    if (need_slots > (int64_t)t->free_slot.size()) return KV_ENOSPC;
-    if (need_hbm > (int64_t)t->free_hbm.size() + drop) return KV_ENOSPC;
-
-    t->oi.clear(); t->os.clear(); t->ii.clear(); t->is.clear(); t->held.clear();
-    int64_t n_drop = 0;
-    for (int32_t i = 0; i < n_pre; i++) {
-        TableReq &r = t->req[(size_t)pre[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            if (r.state[b] == KV_BLOCK_SYNCED) {
-                t->free_hbm.push(r.hbm[b]);  // no byte moves; reusable by this call's swap-ins
-                n_drop++;
-            } else {
-                if (r.slot[b] < 0) {
-                    r.slot[b] = t->free_slot.top();
-                    t->free_slot.pop();
-                }
-                t->oi.push_back(r.hbm[b]);
-                t->os.push_back(r.slot[b]);
-                t->held.push_back(r.hbm[b]);  // a source of this call: not a destination of it
-            }
-            r.hbm[b] = -1;
-            r.state[b] = KV_BLOCK_HOST;
-        }
-        r.resident = false;
-    }
-    for (int32_t i = 0; i < n_res; i++) {
-        TableReq &r = t->req[(size_t)res[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            const int32_t id = t->free_hbm.top();
-            t->free_hbm.pop();
-            r.hbm[b] = id;
-            r.state[b] = KV_BLOCK_SYNCED;
-            t->ii.push_back(id);
-            t->is.push_back(r.slot[b]);
-        }
-        r.resident = true;
-    }
-    for (int32_t id : t->held) t->free_hbm.push(id);
-    t->cnt.copied_preempt += (int64_t)t->oi.size();
-    t->cnt.dropped_synced += n_drop;
-    t->cnt.swapped_in += (int64_t)t->ii.size();
-    // the table's own bookkeeping guarantees what admission checks; a failure here is a HIP error
-    return kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
-                     (int32_t)t->ii.size());
-}
-
-int kv_table_finish(kv_table *t, int32_t rq)
-{
-    if (!t || rq < 0 || rq >= t->max_req || !t->req[(size_t)rq].used) return KV_EINVAL;
-    TableReq &r = t->req[(size_t)rq];
-    for (size_t b = 0; b < r.hbm.size(); b++) {
-        if (r.hbm[b] >= 0) t->free_hbm.push(r.hbm[b]);
-        if (r.slot[b] >= 0) t->free_slot.push(r.slot[b]);
-    }
-    r = TableReq{};
-    return KV_OK;
-}
-
-int kv_table_blocks(kv_table *t, int32_t rq, int32_t *ids, int32_t *slots, int32_t *states, int32_t cap,
-                    int32_t *n, int32_t *info)
-{
-    if (!t || rq < 0 || rq >= t->max_req || !t->req[(size_t)rq].used || !n) return KV_EINVAL;
-    const TableReq &r = t->req[(size_t)rq];
-    if ((ids || slots || states) && (int64_t)r.hbm.size() > cap) return KV_EINVAL;
-    for (size_t b = 0; b < r.hbm.size(); b++) {
-        if (ids) ids[b] = r.hbm[b];
-        if (slots) slots[b] = r.slot[b];
-        if (states) states[b] = r.state[b];
-    }
-    *n = (int32_t)r.hbm.size();
-    if (info) {
-        info[0] = r.len;
-        info[1] = r.resident ? 1 : 0;
-    }
-    return KV_OK;
-}
-
-int kv_table_get_counts(kv_table *t, kv_table_counts *out)
-{
-    if (!t || !out) return KV_EINVAL;
-    *out = t->cnt;
-    out->free_hbm_blocks = (int64_t)t->free_hbm.size();
-    out->free_host_slots = (int64_t)t->free_slot.size();
-    return KV_OK;
-}
-
-// ---- VLT and LVF (host only) --------------------------------------------------------
-double kv_sched_vlt(const kv_sched_params *p, const kv_sched_req *r, double t_now)
-{
-    if (!p || !r) return 0.0;
-    const double idle = t_now - r->t_ref;
-    switch (r->state) {
-    case KV_REQ_ROTARY: return p->alpha * std::max(0.0, idle - p->beta_b * p->slo_tbt);
-    case KV_REQ_WAITING: return std::max(0.0, idle - p->beta_f * p->slo_ttft);
-    default: return -idle;
-    }
-}
-
-int kv_sched_lvf(const kv_sched_params *p, const kv_sched_req *reqs, int32_t n, double t_now, int32_t b_xfer,
-                 int32_t b_hbm, int32_t *preempt, int32_t *n_preempt, int32_t *prioritize, int32_t *n_prioritize,
-                 int32_t *fcfs)
-{
-    if (!p || n < 0 || (n > 0 && !reqs) || b_xfer < 0 || b_hbm < 0 || !n_preempt || !n_prioritize ||
-        (n > 0 && (!preempt || !prioritize)))
-        return KV_EINVAL;
-    int64_t inactive_blocks = 0;
-    for (int32_t i = 0; i < n; i++) {
-        if (reqs[i].state < KV_REQ_RUNNING || reqs[i].state > KV_REQ_ROTARY || reqs[i].blocks < 0) return KV_EINVAL;
-        if (reqs[i].state != KV_REQ_RUNNING) inactive_blocks += reqs[i].blocks;
-    }
-    *n_preempt = *n_prioritize = 0;
-    if (fcfs) *fcfs = 0;
-    std::vector<int32_t> order((size_t)n);
-    for (int32_t i = 0; i < n; i++) order[(size_t)i] = i;
-    if ((int64_t)b_hbm >= inactive_blocks) {  // no contention: first come first served
-        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-            return reqs[a].t_ref != reqs[b].t_ref ? reqs[a].t_ref < reqs[b].t_ref : reqs[a].id < reqs[b].id;
-        });
-        for (int32_t k : order)
-            if (reqs[k].state != KV_REQ_RUNNING) prioritize[(*n_prioritize)++] = reqs[k].id;
-        if (fcfs) *fcfs = 1;
-        return KV_OK;
-    }
-    std::vector<double> vlt((size_t)n);
-    for (int32_t i = 0; i < n; i++) vlt[(size_t)i] = kv_sched_vlt(p, &reqs[i], t_now);
-    std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
-        return vlt[(size_t)a] != vlt[(size_t)b] ? vlt[(size_t)a] > vlt[(size_t)b] : reqs[a].id < reqs[b].id;
-    });
-    int64_t left = (int64_t)b_hbm + b_xfer;
-    for (int32_t k : order) {
-        if (reqs[k].state != KV_REQ_RUNNING && vlt[(size_t)k] >= 0.0 && reqs[k].blocks <= left) {
-            prioritize[(*n_prioritize)++] = reqs[k].id;
-            left -= reqs[k].blocks;
-        }
-    }
-    int64_t swap = (int64_t)b_xfer - left;
-    for (auto it = order.rbegin(); it != order.rend() && swap > 0; ++it) {
-        const int32_t k = *it;
-        if (reqs[k].state == KV_REQ_RUNNING && vlt[(size_t)k] < 0.0) {
-            preempt[(*n_preempt)++] = reqs[k].id;
-            swap -= reqs[k].blocks;
-        }
-    }
     return KV_OK;
 }
 

@@ -1,0 +1,87 @@
+// Internal definitions shared by the engine (duplexkv.hip) and the block table
+// (kv_table.cpp): the engine object itself.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <utility>
+#include <vector>
+
+#include "../../include/duplexkv.h"
+
+namespace dkv {
+
+// Admission marks (host only).
+// mark[] holds (epoch << 2) | bits, bits: 1 = named by the out list, 2 = by the in list.
+struct Marks {
+    std::vector<uint32_t> blk, slot;
+    uint32_t epoch = 0;
+    void reset(size_t nb, size_t ns) { blk.assign(nb, 0); slot.assign(ns, 0); epoch = 0; }
+    void next()
+    {
+        if (++epoch >= (1u << 30)) {
+            std::fill(blk.begin(), blk.end(), 0u);
+            std::fill(slot.begin(), slot.end(), 0u);
+            epoch = 1;
+        }
+    }
+};
+
+constexpr int kRing = 8;  // descriptor sets that may be in flight
+
+inline bool list_bad(const int32_t *p, int32_t n) { return n < 0 || (n > 0 && !p); }
+
+}  // namespace dkv
+
+struct kv_engine {
+    kv_config cfg;
+    int device = 0;
+    uint64_t seg = 0, block_bytes = 0, cache_bytes = 0, pool_bytes = 0;
+    uint32_t n_planes = 0;
+    int vec = 1;  // bytes per lane access
+    uint8_t *hbm = nullptr;
+    uint8_t *pool = nullptr;
+    bool own_pool = false;
+    hipStream_t s_out = nullptr, s_in = nullptr;
+    bool own_streams = false;
+    int n_cus = 0;
+
+    // descriptor ring: per set [out_ids | out_slots | in_ids | in_slots]
+    int32_t *desc_host = nullptr, *desc_dev = nullptr;
+    size_t desc_cap = 0;  // ints per set
+    // ring_out[k] / ring_in[k] are recorded after the last work that reads set k
+    // on each stream; they double as the end-of-work timestamps for the stats
+    hipEvent_t ring_out[dkv::kRing] = {}, ring_in[dkv::kRing] = {};
+    bool ring_out_rec[dkv::kRing] = {}, ring_in_rec[dkv::kRing] = {};
+    int ring_cur = 0;
+
+    dkv::Marks marks;
+    std::vector<std::pair<int32_t, int32_t>> sort_tmp;  // (slot, id)
+
+    // stats
+    hipEvent_t ev_o0 = nullptr, ev_o1 = nullptr, ev_i0 = nullptr, ev_i1 = nullptr, ev_join = nullptr;
+    hipEvent_t b_o0 = nullptr, b_o1 = nullptr, b_i0 = nullptr, b_i1 = nullptr;  // this batch's first start / last end
+    bool batch_open = false;
+    bool out_pending = false, in_pending = false;  // work enqueued since the last kv_wait
+    bool in_dirty = false;                         // stream_in holds work stream_out has not joined
+    bool in_after_out = false;                     // block table in use: in-only work waits for earlier out work
+    double t0 = 0;
+    kv_stats acc{}, last{};
+    int sticky = KV_OK;
+
+    // staging for SDMA_STAGED: one buffer per direction, chunk_cap bytes each.
+    // A direction's pack / copy / unpack all run in order on that direction's
+    // stream, so a buffer is never reused before its last reader is done.
+    uint8_t *stage_out = nullptr, *stage_in = nullptr;
+    uint64_t chunk_cap = 0;
+
+    // synthetic decode reader
+    hipStream_t s_read = nullptr;
+    int32_t *read_ids = nullptr;               // device, 2 * n_hbm_blocks ints
+    int32_t *read_ids_host = nullptr;          // pinned
+    unsigned long long *read_acc = nullptr;    // device: [0] sum, then one 32-bit tile counter per pass
+    unsigned long long *read_acc_host = nullptr;  // pinned
+    std::vector<hipEvent_t> read_ev;           // passes + 1 timestamps
+    int32_t read_passes = 0;
+};
