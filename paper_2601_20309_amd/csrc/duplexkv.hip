@@ -1048,7 +1048,8 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
         HIPTRY(e, hipMemcpyAsync(e->read_ids, e->read_ids_host, (size_t)n * sizeof(int32_t),
                                  hipMemcpyHostToDevice, e->s_read));
     }
-    int wgs = 16 * (e->n_cus > 0 ? e->n_cus : 256);
+    // 8 workgroups of 256 lanes fill a CU; more only queue (measured: 6.26 TB/s at 8 per CU, 6.15 at 16)
+    int wgs = 8 * (e->n_cus > 0 ? e->n_cus : 256);
     if (max_wgs > 0) wgs = std::min(wgs, (int)max_wgs);
     wgs = (int)std::min<uint32_t>((uint32_t)wgs, std::max<uint32_t>(p.tiles, 1u));
     HIPTRY(e, hipEventRecord(e->read_ev[0], e->s_read));
