@@ -295,7 +295,6 @@ int default_wgs(const kv_engine *e, bool link_bound, bool both_directions = true
 int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
 {
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
-    int32_t *dd = e->desc_dev + (size_t)k * e->desc_cap;
     const int u = link_u(e);
     const int lanes = e->cfg.wg_lanes ? e->cfg.wg_lanes : dkv::kThreads;
     MoveParams p = base_params(e, u, lanes);
@@ -305,15 +304,16 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     p.far_slot_stride_in = p.far_slot_stride_out;
     p.far_plane_stride_in = p.far_plane_stride_out;
     p.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
-    int32_t *d_o = dd, *d_i = dd + 2 * (size_t)no;  // each: [ids | slots]
-    int32_t *h_o = dh, *h_i = dh + 2 * (size_t)no;
+    // The link-bound kernels fetch ids and slots with scalar loads straight from the
+    // pinned ring (a few thousand 64-byte reads over a link that moves gigabytes):
+    // no upload, nothing between the call and the launch.
+    int32_t *d_o = dh, *d_i = dh + 2 * (size_t)no;  // each: [ids | slots]
     DirDesc dout{(uint32_t)no, 0, 0, 0}, din{(uint32_t)ni, 0, 0, 0};
     const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
     const MoveIds ids_both{d_o, d_o + no, d_i, d_i + ni};
     if (!dir_tiles((uint32_t)no, p.n_planes, p.tiles_per_seg, dout.tiles) ||
         !dir_tiles((uint32_t)ni, p.n_planes, p.tiles_per_seg, din.tiles))
         return KV_EUNSUP;
-    const size_t ints_out = 2 * (size_t)no, ints_in = 2 * (size_t)ni;
     const DirDesc none{0, 0, 0, 0};
     auto grid = [&](uint32_t tiles, bool both) {
         return (int)std::min<uint32_t>((uint32_t)default_wgs(e, true, both), tiles);
@@ -326,8 +326,6 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
             e->in_dirty = false;
         }
-        HIPTRY(e, hipMemcpyAsync(d_o, h_o, (ints_out + ints_in) * sizeof(int32_t), hipMemcpyHostToDevice,
-                                 e->s_out));
         if (!e->b_o0 && !e->b_i0) {  // one start timestamp serves both directions
             if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
             e->b_i0 = e->b_o0;
@@ -357,7 +355,6 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
             e->in_dirty = false;
         }
-        HIPTRY(e, hipMemcpyAsync(d_o, h_o, ints_out * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         p.out = dout;
         p.in = none;
@@ -373,7 +370,6 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipEventRecord(e->ev_join, e->s_out));
             HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join, 0));
         }
-        HIPTRY(e, hipMemcpyAsync(d_i, h_i, ints_in * sizeof(int32_t), hipMemcpyHostToDevice, e->s_in));
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         p.out = none;
         p.in = din;
