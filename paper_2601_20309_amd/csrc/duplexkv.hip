@@ -278,16 +278,39 @@ int link_u(const kv_engine *e)
     return e->cfg.vecs_per_lane ? e->cfg.vecs_per_lane : 1;
 }
 
-int default_wgs(const kv_engine *e, bool link_bound, bool both_directions = true)
+// Launch shape of a link-bound kernel.  What saturates PCIe Gen5 x16 is bytes
+// in flight, not workgroups, and what a kernel running beside the copy loses
+// grows with those same bytes, so the default is the smallest shape on the
+// plateau (all measured, 256 + 256 MiB of scattered 2 MiB blocks):
+//  - both directions in one launch: 124 one-wave workgroups.  Each lane keeps
+//    two 16-byte vectors per direction in flight (the loop is pipelined one
+//    tile deep): 248 KiB each way.  98.6 GB/s; 96 x 256 lanes gives 97.0 and
+//    takes a co-running HBM-bound reader from 6.3 to 3.9 TB/s instead of 5.3.
+//    Counts that are multiples of 8, the number of XCDs workgroups are dealt
+//    over, are 2 % slower at this size (120: 96.7, 124: 98.6, 128: 96.7), and
+//    between 136 and 200 waves the rate dips to 90-93 GB/s, so the count is
+//    not rounded.
+//  - one direction alone has half the accesses per lane: 64 x 256 lanes
+//    (57.3 GB/s in, 55.4 out, both the link's one-way rate).
+// max_copy_wgs counts workgroups of wg_lanes lanes; set alone it keeps 256-lane
+// workgroups, wg_lanes set alone keeps the total number of lanes.
+void link_shape(const kv_engine *e, bool both_in_one_launch, int &wgs, int &lanes)
 {
-    // Link-bound launches need few workgroups: 96 x 256 lanes, each lane with
-    // two 16-byte vectors per direction in flight (the loop is pipelined one
-    // tile deep), is 768 KiB per direction, which saturates PCIe Gen5 x16 both
-    // ways at once; fewer leave gaps, more only add contention (measured).
-    // One direction alone is served best by 64 (57.5 GB/s in, 55.5 out).
-    // HBM-bound pack / unpack launches want the whole chip.
-    int w = link_bound ? (both_directions ? 96 : 64) : 8 * (e->n_cus > 0 ? e->n_cus : 256);
-    if (e->cfg.max_copy_wgs > 0) w = link_bound ? (int)e->cfg.max_copy_wgs : std::min(w, (int)e->cfg.max_copy_wgs);
+    const int cw = e->cfg.max_copy_wgs, cl = e->cfg.wg_lanes;
+    if (both_in_one_launch) {
+        lanes = cl ? cl : (cw ? dkv::kThreads : 64);
+        wgs = cw ? cw : std::max(1, 124 * 64 / lanes);
+    } else {
+        lanes = cl ? cl : dkv::kThreads;
+        wgs = cw ? cw : std::max(1, 64 * dkv::kThreads / lanes);
+    }
+}
+
+// HBM-bound pack / unpack launches want the whole chip.
+int pack_wgs(const kv_engine *e)
+{
+    int w = 8 * (e->n_cus > 0 ? e->n_cus : 256);
+    if (e->cfg.max_copy_wgs > 0) w = std::min(w, (int)e->cfg.max_copy_wgs);
     return std::max(w, 1);
 }
 
@@ -296,31 +319,39 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
 {
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
     const int u = link_u(e);
-    const int lanes = e->cfg.wg_lanes ? e->cfg.wg_lanes : dkv::kThreads;
-    MoveParams p = base_params(e, u, lanes);
-    p.far_out = e->pool;
-    p.far_in = e->pool;
-    pool_strides(e, p.far_slot_stride_out, p.far_plane_stride_out);
-    p.far_slot_stride_in = p.far_slot_stride_out;
-    p.far_plane_stride_in = p.far_plane_stride_out;
-    p.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
+    const bool fused = path == KV_PATH_FUSED && no > 0 && ni > 0;
+    int wgs1 = 0, lanes1 = 0;  // shape of a launch that carries one direction
+    link_shape(e, false, wgs1, lanes1);
+    auto params = [&](int lanes) {
+        MoveParams q = base_params(e, u, lanes);
+        q.far_out = e->pool;
+        q.far_in = e->pool;
+        pool_strides(e, q.far_slot_stride_out, q.far_plane_stride_out);
+        q.far_slot_stride_in = q.far_slot_stride_out;
+        q.far_plane_stride_in = q.far_plane_stride_out;
+        q.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
+        return q;
+    };
     // The link-bound kernels fetch ids and slots with scalar loads straight from the
     // pinned ring (a few thousand 64-byte reads over a link that moves gigabytes):
     // no upload, nothing between the call and the launch.
     int32_t *d_o = dh, *d_i = dh + 2 * (size_t)no;  // each: [ids | slots]
-    DirDesc dout{(uint32_t)no, 0, 0, 0}, din{(uint32_t)ni, 0, 0, 0};
-    const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
-    const MoveIds ids_both{d_o, d_o + no, d_i, d_i + ni};
-    if (!dir_tiles((uint32_t)no, p.n_planes, p.tiles_per_seg, dout.tiles) ||
-        !dir_tiles((uint32_t)ni, p.n_planes, p.tiles_per_seg, din.tiles))
-        return KV_EUNSUP;
     const DirDesc none{0, 0, 0, 0};
-    auto grid = [&](uint32_t tiles, bool both) {
-        return (int)std::min<uint32_t>((uint32_t)default_wgs(e, true, both), tiles);
+    auto desc = [](const MoveParams &q, int32_t n, DirDesc &d) {
+        d = DirDesc{(uint32_t)n, 0, 0, 0};
+        return dir_tiles((uint32_t)n, q.n_planes, q.tiles_per_seg, d.tiles);
     };
 
-    if (path == KV_PATH_FUSED && no > 0 && ni > 0) {
-        // one launch on stream_out; stream_in is joined before (if it holds work) and after
+    if (fused) {
+        // one launch on stream_out carries both directions; stream_in is joined
+        // before (if it holds work) and after
+        int wgs2 = 0, lanes2 = 0;
+        link_shape(e, true, wgs2, lanes2);
+        MoveParams p = params(lanes2);
+        if (!desc(p, no, p.out) || !desc(p, ni, p.in)) return KV_EUNSUP;
+        // in list longer: spread the out tiles over it instead of pairing 1:1
+        if (p.full_tiles && p.in.tiles > p.out.tiles)
+            p.mix_q = (((uint64_t)p.out.tiles << 32) + p.in.tiles - 1) / p.in.tiles;
         if (e->in_dirty || !e->own_streams) {
             HIPTRY(e, hipEventRecord(e->ev_join, e->s_in));
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
@@ -336,17 +367,21 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
                 e->b_i0 = e->ev_i0;
             }
         }
-        p.out = dout;
-        p.in = din;
-        const int wgs = grid(std::max(dout.tiles, din.tiles), true);
-        launch_move(u, e->vec, wgs, lanes, e->s_out, p, ids_both);
+        launch_move(u, e->vec, (int)std::min<uint32_t>((uint32_t)wgs2, std::max(p.out.tiles, p.in.tiles)), lanes2,
+                    e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni});
         HIPTRY(e, hipGetLastError());
+        e->acc.n_launches += 1;
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->b_i1 = e->ring_out[k];
         HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ring_out[k], 0));
-        e->acc.n_launches += 1;
         return KV_OK;
     }
+    MoveParams p = params(lanes1);
+    DirDesc dout, din;
+    if (!desc(p, no, dout) || !desc(p, ni, din)) return KV_EUNSUP;
+    const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
+    const int lanes = lanes1;
+    auto grid = [&](uint32_t tiles) { return (int)std::min<uint32_t>((uint32_t)wgs1, tiles); };
     // one kernel per direction, each on its own stream
     if (no > 0) {
         if (e->in_after_out && ni == 0 && e->in_dirty) {
@@ -358,7 +393,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         p.out = dout;
         p.in = none;
-        const int wgs = grid(dout.tiles, false);
+        const int wgs = grid(dout.tiles);
         launch_move(u, e->vec, wgs, lanes, e->s_out, p, ids_out);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
@@ -373,7 +408,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         p.out = none;
         p.in = din;
-        const int wgs = grid(din.tiles, false);
+        const int wgs = grid(din.tiles);
         launch_move(u, e->vec, wgs, lanes, e->s_in, p, ids_in);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
@@ -604,7 +639,7 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             MoveParams p = stage_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, U);
             p.out = DirDesc{j1 - co.j0, 0, 1, 0};
             if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
-            const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.out.tiles);
+            const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.out.tiles);
             launch_move(U, e->vec, wgs, dkv::kThreads, e->s_out, p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr});
             HIPTRY(e, hipGetLastError());
             if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
@@ -622,7 +657,7 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             MoveParams p = stage_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, U);
             p.in = DirDesc{j1 - ci.j0, 0, 1, 0};
             if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
-            const int wgs = (int)std::min<uint32_t>((uint32_t)default_wgs(e, false), p.in.tiles);
+            const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.in.tiles);
             launch_move(U, e->vec, wgs, dkv::kThreads, e->s_in, p, MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr});
             HIPTRY(e, hipGetLastError());
             n_ops++;

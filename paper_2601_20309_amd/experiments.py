@@ -328,17 +328,18 @@ def interference():
     link = B.kv_probe_link(256 << 20, 5)
     cache = _cache(shape)
     print(f"\nhipMemcpyAsync pinned peaks: D2H {link['d2h']:.2f}, H2D {link['h2d']:.2f} GB/s\n")
-    print("| rotation path | copy WGs | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
+    print("| rotation path | copy WGs x lanes | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
           "reader alone TB/s | reader beside rotation TB/s |")
     print("|---|---|---|---|---|---|")
-    for path, wgs, contiguous in [(B.KV_PATH_FUSED, 0, False), (B.KV_PATH_FUSED, 48, False),
-                                  (B.KV_PATH_FUSED, 32, False), (B.KV_PATH_FUSED, 16, False),
-                                  (B.KV_PATH_SDMA_STAGED, 0, True)]:
+    for path, wgs, lanes, contiguous in [(B.KV_PATH_FUSED, 0, 0, False), (B.KV_PATH_FUSED, 96, 256, False),
+                                         (B.KV_PATH_FUSED, 100, 64, False), (B.KV_PATH_FUSED, 31, 256, False),
+                                         (B.KV_PATH_FUSED, 25, 256, False), (B.KV_PATH_FUSED, 16, 256, False),
+                                         (B.KV_PATH_SDMA_STAGED, 0, 0, True)]:
         rot = W.config_rotation(name, contiguous_slots=contiguous)
         named = np.zeros(shape.n_hbm_blocks, bool)
         named[rot.out_ids] = True; named[rot.in_ids] = True
         others = np.flatnonzero(~named)[:19200].astype(np.int32)
-        eng = B.Engine(B.make_config(shape, path=path, max_copy_wgs=wgs), cache.data_ptr())
+        eng = B.Engine(B.make_config(shape, path=path, max_copy_wgs=wgs, wg_lanes=lanes), cache.data_ptr())
         blk = B.kv_block_bytes(eng.cfg)
         calls = _rot_calls(eng, rot)
         moved = (len(rot.out_ids) + len(rot.in_ids)) * blk
@@ -374,7 +375,8 @@ def interference():
                 inside = inside[1:] or pm2      # the first one started before the rotation
                 read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
         ms_both = statistics.median(both)
-        print(f"| {B.PATH_NAMES[path]} | {wgs or 'default'} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
+        launch = "—" if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (124 x 64)"
+        print(f"| {B.PATH_NAMES[path]} | {launch} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
               f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
         eng.kv_destroy()
 
@@ -452,7 +454,7 @@ def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slo
                       n_hbm_blocks=hbm_blocks, n_host_slots=host_slots)
     P = shape.block_size
     cache = _cache(shape)
-    eng = B.Engine(B.make_config(shape, max_copy_wgs=32), cache.data_ptr())   # co-running: small footprint
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
     tab = B.Table(eng, 4096)
     blk = B.kv_block_bytes(eng.cfg)
     params = (3.0, 0.0, 0.5, 0.1, 5.0)            # alpha, beta_B, beta_F, S_B = 100 ms, S_F = 5 s (Section 5.1)

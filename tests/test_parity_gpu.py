@@ -236,3 +236,34 @@ def test_dma_blocks_merges_runs_and_needs_block_first_cache():
     case.close()
     with pytest.raises(B.KVError):
         make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_DMA_BLOCKS, rot=rot)     # layer-first cache
+
+
+@pytest.mark.parametrize("hbm_layout", [B.KV_HBM_LAYER_FIRST, B.KV_HBM_BLOCK_FIRST])
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("n_out,n_in", [(160, 8), (8, 160), (170, 30), (30, 170), (99, 100), (1, 199), (85, 100)])
+def test_unbalanced_rotations_in_one_launch(n_out, n_in, layout, hbm_layout):
+    """With the in list longer, the kernel spreads the out tiles evenly over the in
+    tiles instead of pairing them 1:1; with the out list longer, the rest of it
+    follows the paired part.  Either way the result is the same rotation."""
+    sh = W.KVShape(8, 8, 128, 16, n_hbm_blocks=320, n_host_slots=200)   # 512 KiB blocks
+    rot = W.simple_rotation(sh, n_out, n_in, seed=n_out * 1000 + n_in)
+    case, _ = make_case(sh, layout, B.KV_PATH_AUTO, rot=rot, hbm_layout=hbm_layout)
+    case.rotate(rot)
+    case.check()
+    assert case.eng.kv_last_stats()["n_launches"] == 1
+    # and back, as one rotation the other way round
+    case.rotate(rot.inverse())
+    case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("lanes,wgs,u", [(64, 7, 1), (64, 124, 2), (256, 31, 1), (128, 1, 4), (1024, 3, 1)])
+def test_in_heavy_interleave_for_every_launch_shape(lanes, wgs, u):
+    sh = W.SHAPES["small8b"]
+    for n_out, n_in in [(3, 40), (39, 40), (1, 2)]:
+        rot = W.simple_rotation(sh, n_out, n_in, seed=n_out * 100 + n_in + lanes)
+        case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_FUSED, rot=rot, wg_lanes=lanes, max_copy_wgs=wgs,
+                            vecs_per_lane=u)
+        case.rotate(rot)
+        case.check()
+        case.close()

@@ -9,7 +9,8 @@ pytestmark = pytest.mark.gpu
 
 
 def test_cross_iteration_pipeline_runs_and_keeps_synced_blocks_valid():
-    out = X.serve(rps=400.0, seconds=0.8, seed=3, hbm_blocks=768, host_slots=4096)
+    # a fixed link budget: derived from measured times it would make the schedule depend on the box's timing
+    out = X.serve(rps=400.0, seconds=0.8, seed=3, b_xfer=64, hbm_blocks=768, host_slots=4096)
     c = out["counts"]
     assert out["iterations"] > 50
     assert c["swapped_in"] > 0 and c["dropped_synced"] > 0 and c["copied_eager"] > 0
