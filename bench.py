@@ -27,7 +27,7 @@ HBM_PEAK_GBPS = 8000.0
 # of --calibrate-copy (profiles/kv_move_kernel_llama3_8b.txt).  The counters see
 # HBM and host-memory accesses alike: each moved byte is read once and written
 # once, so the algorithmic figure is 2 x (bytes_out + bytes_in).
-MEASURED_TRAFFIC_BYTES = {("llama3_8b", "fused"): 1073931566}
+MEASURED_TRAFFIC_BYTES = {("llama3_8b", "fused"): 1073942424}
 
 
 def log(*a):
@@ -145,7 +145,6 @@ def main():
 
     # expected first-step result from the oracle, on the named blocks only
     if not args.no_check:
-        from oracle import kv_oracle as O
         cv = cache.view(torch.int16)
         before_out = cv[:, :, torch.from_numpy(rot.out_ids).long().cuda()].cpu()   # [L,2,n,P,H,D]
     for i in range(args.warmup + (args.warmup % 2)):   # even count: state returns

@@ -332,10 +332,25 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         q.plane_major = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
         return q;
     };
-    // The link-bound kernels fetch ids and slots with scalar loads straight from the
-    // pinned ring (a few thousand 64-byte reads over a link that moves gigabytes):
-    // no upload, nothing between the call and the launch.
-    int32_t *d_o = dh, *d_i = dh + 2 * (size_t)no;  // each: [ids | slots]
+    // The link-bound kernels fetch ids and slots with scalar loads.  Where one list
+    // entry stands for many tiles (a whole block in block-first pool order) they
+    // read the pinned ring in place: a few thousand 64-byte reads over a link that
+    // moves gigabytes, no upload, nothing between the call and the launch.  Where
+    // an entry stands for little (small segments, few layers, or plane-major
+    // order, in which every segment is its own visit) every workgroup fetches a
+    // new entry nearly every tile; those reads would then be an eighth of the
+    // link traffic (4 KiB segments, one layer: 83 instead of 93 GB/s), so the set
+    // is uploaded first, ~5 us on the launch's stream.
+    const uint64_t visit_bytes = e->cfg.host_layout == KV_HOST_LAYER_FIRST ? e->seg : e->block_bytes;
+    const bool upload = visit_bytes < (256u << 10);
+    int32_t *dd = upload ? e->desc_dev + (size_t)k * e->desc_cap : dh;
+    int32_t *d_o = dd, *d_i = dd + 2 * (size_t)no;  // each: [ids | slots]
+    auto upload_ids = [&](bool out_part, bool in_part, hipStream_t s) -> int {
+        if (!upload) return KV_OK;
+        const size_t a = out_part ? 0 : 2 * (size_t)no, b = in_part ? 2 * ((size_t)no + ni) : 2 * (size_t)no;
+        HIPTRY(e, hipMemcpyAsync(dd + a, dh + a, (b - a) * sizeof(int32_t), hipMemcpyHostToDevice, s));
+        return KV_OK;
+    };
     const DirDesc none{0, 0, 0, 0};
     auto desc = [](const MoveParams &q, int32_t n, DirDesc &d) {
         d = DirDesc{(uint32_t)n, 0, 0, 0};
@@ -357,6 +372,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
             e->in_dirty = false;
         }
+        if (upload_ids(true, true, e->s_out) != KV_OK) return KV_EHIP;
         if (!e->b_o0 && !e->b_i0) {  // one start timestamp serves both directions
             if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
             e->b_i0 = e->b_o0;
@@ -390,6 +406,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
             e->in_dirty = false;
         }
+        if (upload_ids(true, false, e->s_out) != KV_OK) return KV_EHIP;
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         p.out = dout;
         p.in = none;
@@ -405,6 +422,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
             HIPTRY(e, hipEventRecord(e->ev_join, e->s_out));
             HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join, 0));
         }
+        if (upload_ids(false, true, e->s_in) != KV_OK) return KV_EHIP;
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         p.out = none;
         p.in = din;
@@ -973,18 +991,20 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double
     kv_engine *e = nullptr;  // HIPTRY wants one; no engine state here
     void *ha = nullptr, *hb = nullptr, *da = nullptr, *db = nullptr;
     // Streams share a few hardware queues and DMA engines; which pair a process
-    // gets depends on what else it has created.  Five streams are more than
-    // the process has hardware queues; every pairing with stream 0 and 1 is
-    // timed and the best one is reported: the link's ceiling, not a property
-    // of one unlucky pairing.
-    constexpr int kS = 5;
-    hipStream_t st[kS] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    // gets depends on what else it has created.  Up to three rounds of five
+    // streams each (more than the process has hardware queues; earlier rounds'
+    // streams stay alive so that later ones land elsewhere): every pairing with
+    // a round's first two streams is timed and the best one is reported, the
+    // link's ceiling and not a property of one unlucky pairing.  A round that
+    // already shows the directions overlapping ends the search.
+    constexpr int kS = 5, kRounds = 3;
+    hipStream_t st[kS * kRounds] = {};
     auto cleanup = [&]() {
         if (ha) (void)hipHostFree(ha);
         if (hb) (void)hipHostFree(hb);
         if (da) (void)hipFree(da);
         if (db) (void)hipFree(db);
-        for (int i = 0; i < kS; i++)
+        for (int i = 0; i < kS * kRounds; i++)
             if (st[i]) (void)hipStreamDestroy(st[i]);
     };
     if (hipHostMalloc(&ha, bytes, hipHostMallocDefault) != hipSuccess ||
@@ -1014,17 +1034,24 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double
     auto body = [&]() -> int {
         HIPTRY(e, hipMemset(da, 3, bytes));
         HIPTRY(e, hipMemset(db, 4, bytes));
-        for (int i = 0; i < kS; i++) HIPTRY(e, hipStreamCreateWithFlags(&st[i], hipStreamNonBlocking));
-        double ms = 0, best;
-        if (pass(st[0], nullptr, ms) != KV_OK) return KV_EHIP;
-        *d2h = bytes / ms / 1e6;
-        if (pass(nullptr, st[1], ms) != KV_OK) return KV_EHIP;
-        *h2d = bytes / ms / 1e6;
-        best = 1e30;
+        double ms = 0, best = 1e30, one_way = 0;
         const int pairs[7][2] = {{0, 1}, {0, 2}, {0, 3}, {0, 4}, {1, 2}, {1, 3}, {1, 4}};
-        for (auto &pr : pairs) {
-            if (pass(st[pr[0]], st[pr[1]], ms) != KV_OK) return KV_EHIP;
-            best = std::min(best, ms);
+        for (int r = 0; r < kRounds; r++) {
+            hipStream_t *q = st + r * kS;
+            for (int i = 0; i < kS; i++) HIPTRY(e, hipStreamCreateWithFlags(&q[i], hipStreamNonBlocking));
+            if (r == 0) {
+                if (pass(q[0], nullptr, ms) != KV_OK) return KV_EHIP;
+                *d2h = bytes / ms / 1e6;
+                one_way = ms;
+                if (pass(nullptr, q[1], ms) != KV_OK) return KV_EHIP;
+                *h2d = bytes / ms / 1e6;
+                one_way = std::max(one_way, ms);
+            }
+            for (auto &pr : pairs) {
+                if (pass(q[pr[0]], q[pr[1]], ms) != KV_OK) return KV_EHIP;
+                best = std::min(best, ms);
+            }
+            if (best < 1.5 * one_way) break;  // the two copies overlapped
         }
         // both directions are charged the wall time of the pair
         *d2h_duplex = *h2d_duplex = bytes / best / 1e6;

@@ -282,15 +282,24 @@ def configs():
         blk = B.kv_block_bytes(eng.cfg)
         calls = _rot_calls(eng, rot)
 
-        def fn(i):
+        # forward and inverse steps alternate (state returns); an unbalanced rotation is
+        # out-heavy one way and in-heavy the other, so the two are timed apart
+        fwd, bwd = [], []
+        for i in range(2 + 2 * (6 if name == "llama3_8b" else 4)):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
             assert calls[i & 1]() == 0 and eng.kv_wait() == 0
-        ms, ko, ki = _time_calls(eng, fn, 6 if name == "llama3_8b" else 4)
+            if i >= 2:
+                (bwd if i & 1 else fwd).append((time.perf_counter() - t0) * 1e3)
         st = eng.kv_last_stats()
         bo, bi = len(rot.out_ids) * blk, len(rot.in_ids) * blk
-        go, gi = bo / ms / 1e6, bi / ms / 1e6
-        print(f"| {name} | {label} ({B.PATH_NAMES[st['path_used']]}) | {bo / 2**30:.2f} | {bi / 2**30:.2f} | {ms:.3f} | "
-              f"{go:.2f} | {gi:.2f} | {100 * go / link['d2h']:.1f} | {100 * gi / link['h2d']:.1f} | {st['n_launches']} |",
-              flush=True)
+        rows = [(label, statistics.median(fwd + bwd), bo, bi)] if bo == bi else \
+            [(label, statistics.median(fwd), bo, bi), (label + ", the inverse rotation", statistics.median(bwd), bi, bo)]
+        for lab, ms, b_out, b_in in rows:
+            go, gi = b_out / ms / 1e6, b_in / ms / 1e6
+            print(f"| {name} | {lab} ({B.PATH_NAMES[st['path_used']]}) | {b_out / 2**30:.2f} | {b_in / 2**30:.2f} | "
+                  f"{ms:.3f} | {go:.2f} | {gi:.2f} | {100 * go / link['d2h']:.1f} | {100 * gi / link['h2d']:.1f} | "
+                  f"{st['n_launches']} |", flush=True)
         eng.kv_destroy()
     # configs[2] again as 32 back-to-back calls, one request pair each
     shape = W.SHAPES["batch"]
@@ -308,15 +317,22 @@ def configs():
         pairs_f.append(eng.prepare(rot.out_ids[o], rot.out_slots[o], rot.in_ids[i_], rot.in_slots[i_]))
         pairs_b.append(eng.prepare(inv.out_ids[i_], inv.out_slots[i_], inv.in_ids[o], inv.in_slots[o]))
 
-    def fn(i):
+    fwd, bwd = [], []
+    for i in range(10):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
         for c in (pairs_f if i % 2 == 0 else pairs_b):
             assert c() == 0
         assert eng.kv_wait() == 0
-    ms, ko, ki = _time_calls(eng, fn, 4)
+        if i >= 2:
+            (bwd if i & 1 else fwd).append((time.perf_counter() - t0) * 1e3)
     bo, bi = len(rot.out_ids) * blk, len(rot.in_ids) * blk
-    print(f"| batch | default, {len(pairs_f)} calls of one request pair each, one kv_wait | {bo / 2**30:.2f} | {bi / 2**30:.2f} | "
-          f"{ms:.3f} | {bo / ms / 1e6:.2f} | {bi / ms / 1e6:.2f} | {100 * bo / ms / 1e6 / link['d2h']:.1f} | "
-          f"{100 * bi / ms / 1e6 / link['h2d']:.1f} | {eng.kv_last_stats()['n_launches']} |")
+    for lab, ms, b_out, b_in in [("", statistics.median(fwd), bo, bi),
+                                 (", the inverse rotations", statistics.median(bwd), bi, bo)]:
+        print(f"| batch | default, {len(pairs_f)} calls of one request pair each, one kv_wait{lab} | {b_out / 2**30:.2f} | "
+              f"{b_in / 2**30:.2f} | {ms:.3f} | {b_out / ms / 1e6:.2f} | {b_in / ms / 1e6:.2f} | "
+              f"{100 * b_out / ms / 1e6 / link['d2h']:.1f} | {100 * b_in / ms / 1e6 / link['h2d']:.1f} | "
+              f"{eng.kv_last_stats()['n_launches']} |")
     eng.kv_destroy()
 
 
