@@ -267,6 +267,20 @@ int kv_table_eager(kv_table *table, int32_t budget, int32_t *n_done);
 int kv_table_rotate(kv_table *table, const int32_t *preempt, int32_t n_preempt, const int32_t *resume,
                     int32_t n_resume);
 
+/*
+ * kv_table_rotate() and, in the same duplex transfer, kv_table_eager(eager_budget)
+ * over the requests that are resident once the rotation is done: the result
+ * (mappings, states, counters, bytes) is that of the two calls one after the
+ * other.  Why one transfer: with eager block rotation a rotation copies little
+ * out and much in, and on the host link swap-out bytes up to about 0.8 times
+ * the swap-in bytes travel in the time the swap-in needs anyway, so eager
+ * copies issued here cost no link time.  *n_eager (may be NULL) = eager copies
+ * issued.  Errors as kv_table_rotate, and KV_EINVAL for a negative budget;
+ * nothing changes on error.
+ */
+int kv_table_rotate_eager(kv_table *table, const int32_t *preempt, int32_t n_preempt, const int32_t *resume,
+                          int32_t n_resume, int32_t eager_budget, int32_t *n_eager);
+
 /* The request is done: its HBM blocks and host slots are free again (the
  * caller makes sure no transfer of them is still in flight). */
 int kv_table_finish(kv_table *table, int32_t req);

@@ -554,6 +554,19 @@ int okvt_rotate(okvt *t, uint8_t *hbm, uint8_t *pool, const int32_t *pre, int32_
     return OKV_OK;
 }
 
+/* A rotation with the eager step of the requests that stay riding along
+ * (Section 4.3.2: eager copies are issued while other transfers run).  Defined
+ * as what it must equal: the rotation, then the eager step. */
+int okvt_rotate_eager(okvt *t, uint8_t *hbm, uint8_t *pool, const int32_t *pre, int32_t n_pre,
+                      const int32_t *res, int32_t n_res, int32_t eager_budget, int32_t *n_eager)
+{
+    if (n_eager) *n_eager = 0;
+    if (eager_budget < 0) return OKV_EINVAL;
+    int rc = okvt_rotate(t, hbm, pool, pre, n_pre, res, n_res);
+    if (rc != OKV_OK) return rc;
+    return okvt_eager(t, hbm, pool, eager_budget, n_eager);
+}
+
 /* The request is done: its HBM blocks and host slots are free again. */
 int okvt_finish(okvt *t, int32_t req)
 {

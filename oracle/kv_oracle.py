@@ -88,6 +88,9 @@ def lib() -> C.CDLL:
         L.okvt_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, p32]
         L.okvt_rotate.restype = C.c_int
         L.okvt_rotate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, p32, C.c_int32, p32, C.c_int32]
+        L.okvt_rotate_eager.restype = C.c_int
+        L.okvt_rotate_eager.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, p32, C.c_int32, p32, C.c_int32,
+                                        C.c_int32, p32]
         L.okvt_finish.restype = C.c_int
         L.okvt_finish.argtypes = [C.c_void_p, C.c_int32]
         L.okvt_blocks.restype = C.c_int
@@ -214,6 +217,13 @@ class Table:
         pp, np_, k1 = _ids(preempt)
         pr, nr, k2 = _ids(resume)
         return lib().okvt_rotate(self._h, _buf(hbm), _buf(pool), pp, np_, pr, nr)
+
+    def rotate_eager(self, hbm, pool, preempt, resume, budget):
+        pp, np_, k1 = _ids(preempt)
+        pr, nr, k2 = _ids(resume)
+        n = C.c_int32(0)
+        rc = lib().okvt_rotate_eager(self._h, _buf(hbm), _buf(pool), pp, np_, pr, nr, budget, C.byref(n))
+        return rc, n.value
 
     def finish(self, req):
         return lib().okvt_finish(self._h, req)

@@ -28,7 +28,7 @@ PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused"
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
            "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
            "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
-           "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate",
+           "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate", "kv_table_rotate_eager",
            "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_sched_vlt", "kv_sched_lvf",
            "kv_strerror"]
 KV_REQ_RUNNING, KV_REQ_WAITING, KV_REQ_ROTARY = 0, 1, 2
@@ -111,6 +111,8 @@ def _load() -> C.CDLL:
     L.kv_table_eager.argtypes = [C.c_void_p, C.c_int32, p32]
     L.kv_table_rotate.restype = C.c_int
     L.kv_table_rotate.argtypes = [C.c_void_p, p32, C.c_int32, p32, C.c_int32]
+    L.kv_table_rotate_eager.restype = C.c_int
+    L.kv_table_rotate_eager.argtypes = [C.c_void_p, p32, C.c_int32, p32, C.c_int32, C.c_int32, p32]
     L.kv_table_finish.restype = C.c_int
     L.kv_table_finish.argtypes = [C.c_void_p, C.c_int32]
     L.kv_table_blocks.restype = C.c_int
@@ -314,6 +316,13 @@ class Table:
         pp, np_, k1 = _ids(preempt)
         pr, nr, k2 = _ids(resume)
         return lib.kv_table_rotate(self._h, pp, np_, pr, nr)
+
+    def kv_table_rotate_eager(self, preempt, resume, eager_budget: int):
+        pp, np_, k1 = _ids(preempt)
+        pr, nr, k2 = _ids(resume)
+        n = C.c_int32(0)
+        rc = lib.kv_table_rotate_eager(self._h, pp, np_, pr, nr, eager_budget, C.byref(n))
+        return rc, n.value
 
     def kv_table_finish(self, req: int) -> int:
         return lib.kv_table_finish(self._h, req)

@@ -95,21 +95,21 @@ int kv_table_append(kv_table *t, int32_t rq, int32_t n_tokens, int32_t *new_ids,
     return KV_OK;
 }
 
-int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
+// Eager step's choice: up to `budget` FULL blocks of resident requests, by
+// request id, then block index; each gets a slot (its own, else the lowest free
+// one) and is appended to the out list.  Stops when the pool is exhausted.
+static void pick_eager(kv_table *t, int32_t budget, std::vector<std::pair<int32_t, size_t>> &picked,
+                       std::vector<int32_t> &fresh)
 {
-    if (!t || budget < 0) return KV_EINVAL;
-    t->oi.clear();
-    t->os.clear();
-    std::vector<std::pair<int32_t, size_t>> picked;  // (request, block index)
-    std::vector<int32_t> fresh;                      // slots taken for this call
-    for (int32_t q = 0; q < t->max_req && (int32_t)t->oi.size() < budget; q++) {
+    int32_t n = 0;
+    for (int32_t q = 0; q < t->max_req && n < budget; q++) {
         TableReq &r = t->req[(size_t)q];
         if (!r.used || !r.resident) continue;
-        for (size_t i = 0; i < r.hbm.size() && (int32_t)t->oi.size() < budget; i++) {
+        for (size_t i = 0; i < r.hbm.size() && n < budget; i++) {
             if (r.state[i] != KV_BLOCK_FULL) continue;
             int32_t sl = r.slot[i];
             if (sl < 0) {
-                if (t->free_slot.empty()) goto issue;
+                if (t->free_slot.empty()) return;
                 sl = t->free_slot.top();
                 t->free_slot.pop();
                 fresh.push_back(sl);
@@ -117,29 +117,45 @@ int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
             t->oi.push_back(r.hbm[i]);
             t->os.push_back(sl);
             picked.push_back({q, i});
+            n++;
         }
     }
-issue:
+}
+
+static void mark_synced(kv_table *t, const std::vector<std::pair<int32_t, size_t>> &picked, size_t first)
+{
+    for (size_t k = 0; k < picked.size(); k++) {
+        TableReq &r = t->req[(size_t)picked[k].first];
+        r.slot[picked[k].second] = t->os[first + k];
+        r.state[picked[k].second] = KV_BLOCK_SYNCED;
+    }
+}
+
+int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
+{
+    if (!t || budget < 0) return KV_EINVAL;
+    t->oi.clear();
+    t->os.clear();
+    std::vector<std::pair<int32_t, size_t>> picked;  // (request, block index)
+    std::vector<int32_t> fresh;                      // slots taken for this call
+    pick_eager(t, budget, picked, fresh);
     if (!t->oi.empty()) {
         int rc = kv_swap_out(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size());
         if (rc != KV_OK) {
             for (int32_t sl : fresh) t->free_slot.push(sl);
             return rc;
         }
-        for (size_t k = 0; k < picked.size(); k++) {
-            TableReq &r = t->req[(size_t)picked[k].first];
-            r.slot[picked[k].second] = t->os[k];
-            r.state[picked[k].second] = KV_BLOCK_SYNCED;
-        }
+        mark_synced(t, picked, 0);
     }
     t->cnt.copied_eager += (int64_t)t->oi.size();
     if (n_done) *n_done = (int32_t)t->oi.size();
     return KV_OK;
 }
 
-int kv_table_rotate(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res)
+static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res,
+                       int32_t eager_budget, int32_t *n_eager)
 {
-    if (!t || list_bad(pre, n_pre) || list_bad(res, n_res)) return KV_EINVAL;
+    if (!t || list_bad(pre, n_pre) || list_bad(res, n_res) || eager_budget < 0) return KV_EINVAL;
     // who is named, and is each one in the right place
     int rc = KV_OK;
     for (int32_t i = 0; i < n_pre && rc == KV_OK; i++) {
@@ -210,9 +226,31 @@ int kv_table_rotate(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_
     t->cnt.copied_preempt += (int64_t)t->oi.size();
     t->cnt.dropped_synced += n_drop;
     t->cnt.swapped_in += (int64_t)t->ii.size();
+    // the eager step of the requests that stay, riding in the same transfer
+    const size_t n_preempt_copies = t->oi.size();
+    std::vector<std::pair<int32_t, size_t>> picked;
+    std::vector<int32_t> fresh;
+    if (eager_budget > 0) {
+        pick_eager(t, eager_budget, picked, fresh);
+        mark_synced(t, picked, n_preempt_copies);
+        t->cnt.copied_eager += (int64_t)picked.size();
+    }
+    if (n_eager) *n_eager = (int32_t)picked.size();
     // the table's own bookkeeping guarantees what admission checks; a failure here is a HIP error
     return kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
                      (int32_t)t->ii.size());
+}
+
+int kv_table_rotate(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res)
+{
+    return rotate_impl(t, pre, n_pre, res, n_res, 0, nullptr);
+}
+
+int kv_table_rotate_eager(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res,
+                          int32_t eager_budget, int32_t *n_eager)
+{
+    if (n_eager) *n_eager = 0;
+    return rotate_impl(t, pre, n_pre, res, n_res, eager_budget, n_eager);
 }
 
 int kv_table_finish(kv_table *t, int32_t rq)

@@ -32,6 +32,8 @@ int okvt_append(okvt *t, int32_t req, int32_t n_tokens, int32_t *new_ids, int32_
 int okvt_eager(okvt *t, uint8_t *hbm, uint8_t *pool, int32_t budget, int32_t *n_done);
 int okvt_rotate(okvt *t, uint8_t *hbm, uint8_t *pool, const int32_t *pre, int32_t n_pre, const int32_t *res,
                 int32_t n_res);
+int okvt_rotate_eager(okvt *t, uint8_t *hbm, uint8_t *pool, const int32_t *pre, int32_t n_pre, const int32_t *res,
+                      int32_t n_res, int32_t eager_budget, int32_t *n_eager);
 int okvt_finish(okvt *t, int32_t req);
 int okvt_blocks(const okvt *t, int32_t req, int32_t *ids, int32_t *slots, int32_t *states, int32_t cap, int32_t *n,
                 int32_t *info);
@@ -223,10 +225,25 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
             }
             if (rng() % 150 == 0 && !pre.empty()) res.push_back(pre[0]);  // named twice
             if (rng() % 150 == 0) pre.push_back(max_req + 3);             // out of range
-            const int rl = kv_table_rotate(p.lib, pre.data(), (int32_t)pre.size(), res.data(), (int32_t)res.size());
-            const int ro = okvt_rotate(p.ora, p.o_hbm.data(), p.o_pool.data(), pre.data(), (int32_t)pre.size(),
-                                       res.data(), (int32_t)res.size());
-            CHECK(rl == ro, "step %ld rotate(%zu,%zu): %d, oracle %d", step, pre.size(), res.size(), rl, ro);
+            int rl, ro;
+            if (rng() % 2) {
+                rl = kv_table_rotate(p.lib, pre.data(), (int32_t)pre.size(), res.data(), (int32_t)res.size());
+                ro = okvt_rotate(p.ora, p.o_hbm.data(), p.o_pool.data(), pre.data(), (int32_t)pre.size(), res.data(),
+                                 (int32_t)res.size());
+            } else {  // the eager step in the same transfer
+                op = "rotate_eager";
+                const int32_t budget = (int32_t)(rng() % 7) - (rng() % 41 == 0);
+                int32_t ln = -7, on = -7;
+                const int64_t before = g_transfers;
+                rl = kv_table_rotate_eager(p.lib, pre.data(), (int32_t)pre.size(), res.data(), (int32_t)res.size(),
+                                           budget, &ln);
+                ro = okvt_rotate_eager(p.ora, p.o_hbm.data(), p.o_pool.data(), pre.data(), (int32_t)pre.size(),
+                                       res.data(), (int32_t)res.size(), budget, &on);
+                CHECK(ln == on, "step %ld rotate_eager: %d eager copies, oracle %d", step, ln, on);
+                CHECK(g_transfers - before == (rl == KV_OK ? 1 : 0), "rotate_eager issued %ld transfers",
+                      (long)(g_transfers - before));
+            }
+            CHECK(rl == ro, "step %ld %s(%zu,%zu): %d, oracle %d", step, op, pre.size(), res.size(), rl, ro);
             if (rl != KV_OK) failed_ops++;
         } else {
             op = "finish";

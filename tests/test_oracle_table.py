@@ -213,10 +213,42 @@ def test_random_schedules_preserve_every_token(layout, seed):
         elif op <= 8:
             pre = [r for r in resident if rng.random() < 0.4]
             res = [r for r in rotary if rng.random() < 0.5]
-            rc = o.t.rotate(o.u8(o.cache), o.u8(o.pool), pre, res)
+            if rng.random() < 0.5:
+                rc = o.t.rotate(o.u8(o.cache), o.u8(o.pool), pre, res)
+            else:
+                rc, _ = o.t.rotate_eager(o.u8(o.cache), o.u8(o.pool), pre, res, int(rng.integers(0, 6)))
             assert rc in (O.OK, O.ENOSPC)
         elif reqs:
             o.finish(int(rng.choice(reqs)))
         o.check()
     c = o.t.counts()
     assert c["copied_eager"] > 0 and c["copied_preempt"] > 0 and c["dropped_synced"] > 0 and c["swapped_in"] > 0
+
+
+def test_rotation_with_the_eager_step_riding_along():
+    """Request 0 leaves, request 1 comes back, and request 2, which stays, gets its
+    full blocks copied out in the same call: counted as eager copies, SYNCED
+    afterwards, and the whole outcome is that of a rotation followed by an eager step."""
+    sh = W.KVShape(2, 2, 8, 4, n_hbm_blocks=16, n_host_slots=24)
+    a, b = OracleSide(sh, O.BLOCK_FIRST, seed=5), OracleSide(sh, O.BLOCK_FIRST, seed=5)
+    for o in (a, b):
+        o.append(0, 9)                      # 3 blocks, the last one partly filled
+        o.append(1, 8)
+        o.rotate([1], [])                   # request 1 waits in DRAM
+        o.append(2, 14)                     # 4 blocks, 3 of them full, never synced
+    rc, n = a.t.rotate_eager(a.u8(a.cache), a.u8(a.pool), [0], [1], 2)
+    assert (rc, n) == (O.OK, 2)
+    assert a.t.blocks(2)["states"] == [SYNCED, SYNCED, FULL, DIRTY]
+    assert a.t.blocks(0)["states"] == [HOST] * 3 and a.t.blocks(1)["states"] == [SYNCED] * 2
+    b.rotate([0], [1])
+    assert b.eager(2) == 2
+    assert a.t.counts() == b.t.counts()
+    for r in range(3):
+        assert a.t.blocks(r) == b.t.blocks(r)
+    assert np.array_equal(a.cache, b.cache) and np.array_equal(a.pool, b.pool)
+    a.check()
+    # errors change nothing, and a negative budget is one
+    snap = (a.cache.copy(), a.pool.copy(), a.t.counts())
+    assert a.t.rotate_eager(a.u8(a.cache), a.u8(a.pool), [1], [0], -1)[0] == O.EINVAL
+    assert a.t.rotate_eager(a.u8(a.cache), a.u8(a.pool), [0], [], 3)[0] == O.EINVAL   # 0 is not resident
+    assert np.array_equal(snap[0], a.cache) and np.array_equal(snap[1], a.pool) and snap[2] == a.t.counts()

@@ -74,6 +74,12 @@ class BothSides:
         assert rc_o == rc_g, (rc_o, rc_g)
         return rc_o
 
+    def rotate_eager(self, pre, res, budget):
+        rc_o, n_o = self.ot.rotate_eager(self.u8(self.ref_cache), self.u8(self.ref_pool), pre, res, budget)
+        rc_g, n_g = self.gt.kv_table_rotate_eager(pre, res, budget)
+        assert (rc_o, n_o) == (rc_g, n_g), (rc_o, n_o, rc_g, n_g)
+        return rc_o, n_o
+
     def finish(self, req):
         assert self.eng.kv_wait() == 0
         rc_o, rc_g = self.ot.finish(req), self.gt.kv_table_finish(req)
@@ -167,7 +173,11 @@ def test_random_schedules_match_the_oracle(layout, seed):
         elif op <= 5:
             s.eager(int(rng.integers(0, 5)))
         elif op <= 8:
-            s.rotate([r for r in resident if rng.random() < 0.4], [r for r in rotary if rng.random() < 0.5])
+            pre, res = [r for r in resident if rng.random() < 0.4], [r for r in rotary if rng.random() < 0.5]
+            if rng.random() < 0.5:
+                s.rotate(pre, res)
+            else:
+                s.rotate_eager(pre, res, int(rng.integers(0, 6)))
         elif reqs:
             s.finish(int(rng.choice(reqs)))
         if step % 10 == 9:
@@ -237,4 +247,27 @@ def test_back_to_back_table_calls_without_waiting():
         s.rotate([], [1])
         # all four are resident again; nothing was waited for in between
     s.check(6)
+    s.close()
+
+
+def test_eager_copies_ride_in_the_rotation_transfer():
+    """Llama shape: two requests leave (synced but for their tails), two come back, and
+    the eager step of a third, which stays, goes out in the same launch."""
+    sh = W.KVShape(32, 8, 128, 16, n_hbm_blocks=512, n_host_slots=512)
+    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=8)
+    P = sh.block_size
+    for r in (0, 1, 2, 3):
+        assert s.append(r, 20 * P + 3) == 0           # 20 full blocks and a tail each
+    assert s.eager(200) == 80
+    assert s.rotate([2, 3], []) == 0                  # 2 and 3 wait in DRAM
+    assert s.append(4, 40 * P + 5) == 0               # 40 full blocks, never synced
+    s.check()
+    rc, n = s.rotate_eager([0, 1], [2, 3], 30)
+    assert (rc, n) == (0, 30)
+    s.check()
+    st = s.eng.kv_last_stats()
+    assert st["n_launches"] == 1                      # one transfer: 2 tails + 30 eager out, 42 in
+    blk = B.kv_block_bytes(s.cfg)
+    assert st["bytes_out"] == 32 * blk and st["bytes_in"] == 42 * blk
+    assert s.gt.kv_table_blocks(4)["states"][:31] == [O.SYNCED] * 30 + [O.FULL]
     s.close()
