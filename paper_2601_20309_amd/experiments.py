@@ -423,16 +423,18 @@ def reader():
 def eager():
     """What eager block rotation buys at a preemption (Section 4.3.2): 8 requests
     of 4096 tokens leave while 8 others come back, Llama-3-8B shape, with and
-    without the background copies having been issued beforehand."""
-    shape = W.SHAPES["interference"]
+    without the background copies having been issued beforehand; and what the
+    eager copies of 6 further requests cost when they ride in that rotation."""
+    base = W.SHAPES["interference"]
+    shape = W.KVShape(base.n_layers, base.n_kv_heads, base.head_dim, base.block_size,
+                      n_hbm_blocks=base.n_hbm_blocks, n_host_slots=8192)
     cache = _cache(shape)
     print("\n| eager step before the rotation | blocks copied out at preemption | dropped without a copy | "
-          "blocks swapped in | rotation ms | out GiB | in GiB |")
-    print("|---|---|---|---|---|---|---|")
-    for do_eager in (False, True):
+          "eager copies riding along | blocks swapped in | rotation ms | out GiB | in GiB |")
+    print("|---|---|---|---|---|---|---|---|")
+    for do_eager, ride in ((False, 0), (True, 0), (True, 1536)):
         eng = B.Engine(B.make_config(shape), cache.data_ptr())
         tab = B.Table(eng, 32)
-        blk = B.kv_block_bytes(eng.cfg)
         for r in range(16):
             assert tab.kv_table_append(r, 4096 - 5)[0] == 0      # 255 full blocks + a dirty tail
         assert tab.kv_table_rotate(list(range(8, 16)), []) == 0   # 8 requests wait in DRAM
@@ -443,17 +445,20 @@ def eager():
             rc, n = tab.kv_table_eager(1 << 30)
             assert rc == 0 and eng.kv_wait() == 0
             t_eager = (time.perf_counter() - t0) * 1e3
+        for r in range(16, 22 if ride else 16):
+            assert tab.kv_table_append(r, 4096)[0] == 0           # 256 full blocks each, not yet copied
         c0 = tab.kv_table_get_counts()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        assert tab.kv_table_rotate(list(range(8)), list(range(8, 16))) == 0
-        assert eng.kv_wait() == 0
+        rc, n_ride = tab.kv_table_rotate_eager(list(range(8)), list(range(8, 16)), ride)
+        assert rc == 0 and n_ride == ride and eng.kv_wait() == 0
         ms = (time.perf_counter() - t0) * 1e3
         c1 = tab.kv_table_get_counts()
         st = eng.kv_last_stats()
         label = f"yes ({n} blocks, {t_eager:.1f} ms in the background)" if do_eager else "no"
         print(f"| {label} | {c1['copied_preempt'] - c0['copied_preempt']} | {c1['dropped_synced'] - c0['dropped_synced']} | "
-              f"{c1['swapped_in'] - c0['swapped_in']} | {ms:.2f} | {st['bytes_out'] / 2**30:.3f} | {st['bytes_in'] / 2**30:.3f} |")
+              f"{n_ride} | {c1['swapped_in'] - c0['swapped_in']} | {ms:.2f} | {st['bytes_out'] / 2**30:.3f} | "
+              f"{st['bytes_in'] / 2**30:.3f} |", flush=True)
         tab.kv_table_destroy()
         eng.kv_destroy()
 
