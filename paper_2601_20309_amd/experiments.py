@@ -1,7 +1,7 @@
 """Measurements beyond bench.py's headline line, on one MI355X:
 
   python -m paper_2601_20309_amd.experiments ladder        # analogue of the paper's Table 2
-  python -m paper_2601_20309_amd.experiments configs       # configs[1..3] of the benchmark spec, default path
+  python -m paper_2601_20309_amd.experiments configs       # the headline, batch and long-context rotations, default path
   python -m paper_2601_20309_amd.experiments interference  # configs[4]: rotation beside a decode reader
   python -m paper_2601_20309_amd.experiments reader        # the decode reader alone (profiling target)
   python -m paper_2601_20309_amd.experiments eager         # a preemption with and without eager block rotation
@@ -350,12 +350,15 @@ def interference():
     for path, wgs, lanes, contiguous in [(B.KV_PATH_FUSED, 0, 0, False), (B.KV_PATH_FUSED, 96, 256, False),
                                          (B.KV_PATH_FUSED, 100, 64, False), (B.KV_PATH_FUSED, 31, 256, False),
                                          (B.KV_PATH_FUSED, 25, 256, False), (B.KV_PATH_FUSED, 16, 256, False),
-                                         (B.KV_PATH_SDMA_STAGED, 0, 0, True)]:
+                                         (B.KV_PATH_SDMA_STAGED, 0, 0, True), (B.KV_PATH_DMA_BLOCKS, 0, 0, False)]:
         rot = W.config_rotation(name, contiguous_slots=contiguous)
         named = np.zeros(shape.n_hbm_blocks, bool)
         named[rot.out_ids] = True; named[rot.in_ids] = True
         others = np.flatnonzero(~named)[:19200].astype(np.int32)
-        eng = B.Engine(B.make_config(shape, path=path, max_copy_wgs=wgs, wg_lanes=lanes), cache.data_ptr())
+        # one DMA copy per block needs whole blocks to be contiguous: the block-first cache
+        hbm_layout = B.KV_HBM_BLOCK_FIRST if path == B.KV_PATH_DMA_BLOCKS else B.KV_HBM_LAYER_FIRST
+        eng = B.Engine(B.make_config(shape, path=path, max_copy_wgs=wgs, wg_lanes=lanes, hbm_layout=hbm_layout),
+                       cache.data_ptr())
         blk = B.kv_block_bytes(eng.cfg)
         calls = _rot_calls(eng, rot)
         moved = (len(rot.out_ids) + len(rot.in_ids)) * blk
@@ -391,7 +394,8 @@ def interference():
                 inside = inside[1:] or pm2      # the first one started before the rotation
                 read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
         ms_both = statistics.median(both)
-        launch = "—" if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (124 x 64)"
+        launch = ("no kernel, block-first cache" if path == B.KV_PATH_DMA_BLOCKS else "pack / unpack kernels"
+                  if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (124 x 64)")
         print(f"| {B.PATH_NAMES[path]} | {launch} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
               f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
         eng.kv_destroy()
