@@ -67,6 +67,7 @@ bool config_ok(const kv_config *c)
 
 // ---- admission (host only) ------------------------------------------------
 using dkv::Marks;
+using dkv::kClaimStride;
 using dkv::kRing;
 using dkv::list_bad;
 
@@ -144,12 +145,17 @@ struct MoveIds {
     const int32_t *out_ids, *out_slots, *in_ids, *in_slots;
 };
 
-template <int U>
+// `wgs` workgroups of `lanes` lanes; the waves among them are the workers, and
+// no more of them are launched than the launch has steps.
+template <int U, bool LINK>
 void launch_move_v(int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
 {
+    const uint32_t steps = p.mix_q ? p.in.tiles : std::max(p.out.tiles, p.in.tiles);
+    const uint32_t waves_per_wg = (uint32_t)lanes / dkv::kWave;
+    wgs = (int)std::max<uint32_t>(1u, std::min<uint32_t>((uint32_t)wgs, (steps + waves_per_wg - 1) / waves_per_wg));
     dim3 g((unsigned)wgs), b((unsigned)lanes);
 #define DKV_LAUNCH(V) \
-    hipLaunchKernelGGL((dkv::kv_move_kernel<V, U>), g, b, 0, s, p, d.out_ids, d.out_slots, d.in_ids, d.in_slots)
+    hipLaunchKernelGGL((dkv::kv_move_kernel<V, U, LINK>), g, b, 0, s, p, d.out_ids, d.out_slots, d.in_ids, d.in_slots)
     switch (vec) {
     case 16: DKV_LAUNCH(dkv::u32x4); break;
     case 8: DKV_LAUNCH(dkv::u32x2); break;
@@ -160,13 +166,23 @@ void launch_move_v(int vec, int wgs, int lanes, hipStream_t s, const MoveParams 
 #undef DKV_LAUNCH
 }
 
-void launch_move(int u, int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d)
+// link: the far side is host memory (zero-copy paths); else HBM staging.
+void launch_move(int u, int vec, int wgs, int lanes, hipStream_t s, const MoveParams &p, const MoveIds &d, bool link)
 {
-    switch (u) {
-    case 1: launch_move_v<1>(vec, wgs, lanes, s, p, d); break;
-    case 2: launch_move_v<2>(vec, wgs, lanes, s, p, d); break;
-    case 4: launch_move_v<4>(vec, wgs, lanes, s, p, d); break;
-    default: launch_move_v<8>(vec, wgs, lanes, s, p, d); break;
+    if (link) {
+        switch (u) {
+        case 1: launch_move_v<1, true>(vec, wgs, lanes, s, p, d); break;
+        case 2: launch_move_v<2, true>(vec, wgs, lanes, s, p, d); break;
+        case 4: launch_move_v<4, true>(vec, wgs, lanes, s, p, d); break;
+        default: launch_move_v<8, true>(vec, wgs, lanes, s, p, d); break;
+        }
+    } else {
+        switch (u) {
+        case 1: launch_move_v<1, false>(vec, wgs, lanes, s, p, d); break;
+        case 2: launch_move_v<2, false>(vec, wgs, lanes, s, p, d); break;
+        case 4: launch_move_v<4, false>(vec, wgs, lanes, s, p, d); break;
+        default: launch_move_v<8, false>(vec, wgs, lanes, s, p, d); break;
+        }
     }
 }
 
@@ -182,7 +198,7 @@ void hbm_strides(const kv_engine *e, uint64_t &plane_stride, uint64_t &block_str
 }
 
 // Fills the fields common to every launch; `u` = vectors per lane per tile.
-MoveParams base_params(const kv_engine *e, int u, int lanes = dkv::kThreads)
+MoveParams base_params(const kv_engine *e, int u)
 {
     MoveParams p{};
     p.hbm = e->hbm;
@@ -191,7 +207,7 @@ MoveParams base_params(const kv_engine *e, int u, int lanes = dkv::kThreads)
     p.plane0 = 0;
     p.n_planes = e->n_planes;
     p.vec_per_seg = (uint32_t)(e->seg / (uint64_t)e->vec);
-    const uint32_t tile = (uint32_t)lanes * (uint32_t)u;
+    const uint32_t tile = (uint32_t)dkv::kWave * (uint32_t)u;
     p.tiles_per_seg = (p.vec_per_seg + tile - 1) / tile;
     p.full_tiles = p.vec_per_seg % tile == 0 ? 1u : 0u;
     return p;
@@ -322,8 +338,9 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     const bool fused = path == KV_PATH_FUSED && no > 0 && ni > 0;
     int wgs1 = 0, lanes1 = 0;  // shape of a launch that carries one direction
     link_shape(e, false, wgs1, lanes1);
-    auto params = [&](int lanes) {
-        MoveParams q = base_params(e, u, lanes);
+    auto params = [&](unsigned int *claim) {
+        MoveParams q = base_params(e, u);
+        q.claim = claim;
         q.far_out = e->pool;
         q.far_in = e->pool;
         pool_strides(e, q.far_slot_stride_out, q.far_plane_stride_out);
@@ -362,7 +379,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         // before (if it holds work) and after
         int wgs2 = 0, lanes2 = 0;
         link_shape(e, true, wgs2, lanes2);
-        MoveParams p = params(lanes2);
+        MoveParams p = params(e->claim);
         if (!desc(p, no, p.out) || !desc(p, ni, p.in)) return KV_EUNSUP;
         // in list longer: spread the out tiles over it instead of pairing 1:1
         if (p.full_tiles && p.in.tiles > p.out.tiles)
@@ -383,8 +400,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
                 e->b_i0 = e->ev_i0;
             }
         }
-        launch_move(u, e->vec, (int)std::min<uint32_t>((uint32_t)wgs2, std::max(p.out.tiles, p.in.tiles)), lanes2,
-                    e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni});
+        launch_move(u, e->vec, wgs2, lanes2, e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni}, true);
         HIPTRY(e, hipGetLastError());
         e->acc.n_launches += 1;
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
@@ -392,12 +408,10 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ring_out[k], 0));
         return KV_OK;
     }
-    MoveParams p = params(lanes1);
+    MoveParams p = params(e->claim);
     DirDesc dout, din;
     if (!desc(p, no, dout) || !desc(p, ni, din)) return KV_EUNSUP;
     const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
-    const int lanes = lanes1;
-    auto grid = [&](uint32_t tiles) { return (int)std::min<uint32_t>((uint32_t)wgs1, tiles); };
     // one kernel per direction, each on its own stream
     if (no > 0) {
         if (e->in_after_out && ni == 0 && e->in_dirty) {
@@ -410,8 +424,8 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         p.out = dout;
         p.in = none;
-        const int wgs = grid(dout.tiles);
-        launch_move(u, e->vec, wgs, lanes, e->s_out, p, ids_out);
+        p.claim = e->claim;  // launches on stream_out draw from the first pair of counters
+        launch_move(u, e->vec, wgs1, lanes1, e->s_out, p, ids_out, true);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
@@ -426,8 +440,8 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         p.out = none;
         p.in = din;
-        const int wgs = grid(din.tiles);
-        launch_move(u, e->vec, wgs, lanes, e->s_in, p, ids_in);
+        p.claim = e->claim + kClaimStride;  // launches on stream_in from the second
+        launch_move(u, e->vec, wgs1, lanes1, e->s_in, p, ids_in, true);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
@@ -658,7 +672,8 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             p.out = DirDesc{j1 - co.j0, 0, 1, 0};
             if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.out.tiles);
-            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_out, p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr});
+            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_out, p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr},
+                        false);
             HIPTRY(e, hipGetLastError());
             if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
                 return KV_EHIP;
@@ -676,7 +691,8 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             p.in = DirDesc{j1 - ci.j0, 0, 1, 0};
             if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
             const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.in.tiles);
-            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_in, p, MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr});
+            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_in, p, MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr},
+                        false);
             HIPTRY(e, hipGetLastError());
             n_ops++;
             ci.p0 = p1;
@@ -768,6 +784,7 @@ void free_engine(kv_engine *e)
     for (hipEvent_t &x : e->read_ev) ev(x);
     if (e->desc_host) (void)hipHostFree(e->desc_host);
     if (e->desc_dev) (void)hipFree(e->desc_dev);
+    if (e->claim) (void)hipFree(e->claim);
     if (e->own_pool && e->pool) (void)hipHostFree(e->pool);
     if (e->own_streams) {
         if (e->s_out) (void)hipStreamDestroy(e->s_out);
@@ -893,10 +910,13 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
     e->desc_cap = 2 * (size_t)std::min(cfg->n_hbm_blocks, cfg->n_host_slots) + 16;
     if (hipHostMalloc((void **)&e->desc_host, kRing * e->desc_cap * sizeof(int32_t), hipHostMallocDefault) !=
             hipSuccess ||
-        hipMalloc((void **)&e->desc_dev, kRing * e->desc_cap * sizeof(int32_t)) != hipSuccess) {
+        hipMalloc((void **)&e->desc_dev, kRing * e->desc_cap * sizeof(int32_t)) != hipSuccess ||
+        hipMalloc((void **)&e->claim, 2 * kClaimStride * sizeof(unsigned int)) != hipSuccess) {
         (void)hipGetLastError();
         return fail(KV_ENOMEM);
     }
+    // the tile counters start at zero; every launch leaves them at zero again
+    if (hipMemset(e->claim, 0, 2 * kClaimStride * sizeof(unsigned int)) != hipSuccess) return fail(KV_EHIP);
     bool ok = true;
     for (int k = 0; k < kRing; k++) {
         ok = ok && hipEventCreate(&e->ring_out[k]) == hipSuccess;

@@ -29,6 +29,9 @@ struct Marks {
 };
 
 constexpr int kRing = 8;  // descriptor sets that may be in flight
+// Tile counters of the link-bound kernels: one pair per stream (launches on a
+// stream run one after the other), each pair in a 256-byte stretch of its own.
+constexpr int kClaimStride = 64;
 
 inline bool list_bad(const int32_t *p, int32_t n) { return n < 0 || (n > 0 && !p); }
 
@@ -50,6 +53,7 @@ struct kv_engine {
     // descriptor ring: per set [out_ids | out_slots | in_ids | in_slots]
     int32_t *desc_host = nullptr, *desc_dev = nullptr;
     size_t desc_cap = 0;  // ints per set
+    unsigned int *claim = nullptr;  // device: [0..1] for stream_out's launches, [kClaimStride..+1] for stream_in's
     // ring_out[k] / ring_in[k] are recorded after the last work that reads set k
     // on each stream; they double as the end-of-work timestamps for the stats
     hipEvent_t ring_out[dkv::kRing] = {}, ring_in[dkv::kRing] = {};

@@ -2,10 +2,10 @@
 //
 // Everything here is data movement: no MFMA, no arithmetic beyond addressing.
 // One kernel family, kv_move_kernel, serves every use:
-//   - duplex rotation in ONE launch: each thread alternates a 16-byte move
+//   - duplex rotation in ONE launch: each lane alternates a 16-byte move
 //     HBM->host with a 16-byte move host->HBM, which keeps the two PCIe
 //     directions locked 1:1 (measured faster in duplex than two independent
-//     kernels, and equal to the DMA engines' duplex rate);
+//     kernels, and above the DMA engines' duplex rate);
 //   - a single direction (the other list empty): zero-copy swap-out or swap-in;
 //   - pack / unpack between the scattered cache and a contiguous staging
 //     buffer in HBM (the "far" side is then device memory, slot = list index).
@@ -18,8 +18,9 @@ namespace dkv {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
+constexpr int kWave = 64;          // a wave is the unit of work: one tile at a time
 constexpr int kThreads = 256;      // default lanes per workgroup (4 waves)
-constexpr int kMaxThreads = 1024;  // the move kernels take their tile width from blockDim.x, up to this
+constexpr int kMaxThreads = 1024;  // workgroups only pack waves; any multiple of 64 up to this
 
 // One direction's block list as the kernel sees it.  The id arrays themselves
 // are separate __restrict__ kernel arguments so that the compiler fetches them
@@ -47,12 +48,15 @@ struct MoveParams {
     uint32_t plane0;         // first plane this launch covers
     uint32_t n_planes;       // planes this launch covers
     uint32_t vec_per_seg;    // seg_bytes / sizeof(V)
-    uint32_t tiles_per_seg;  // ceil(vec_per_seg / (lanes per workgroup * U))
+    uint32_t tiles_per_seg;  // ceil(vec_per_seg / (64 * U))
     uint32_t plane_major;    // tile order: 1 = [plane][i][tile], 0 = [i][plane][tile]
     uint32_t full_tiles;     // 1: vec_per_seg is a multiple of the tile, no lane is ever out of range
     // 0, or ceil(out.tiles * 2^32 / in.tiles) when the in list is the longer one and
-    // the out tiles are to be spread evenly over it (see run_in_heavy)
+    // the out tiles are to be spread evenly over it (see make_job)
     uint64_t mix_q;
+    // nullptr: wave w of W takes tiles w, w + W, ...; else two counters in device
+    // memory, zero at launch, [0] the next unclaimed tile, [1] the waves that are done
+    unsigned int *claim;
     DirDesc out, in;
 };
 
@@ -80,211 +84,202 @@ __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d,
     far_off = (uint64_t)slot * slot_stride + (uint64_t)pl * plane_stride + (uint64_t)tin * tile_bytes;
 }
 
-// Everything one lane needs to move its share of one tile.  Which directions
-// take part is a compile-time property of the loop the tile belongs to, so the
-// hot loops are straight-line code and the compiler can count exactly how many
-// loads may stay in flight at each store.
+// What one wave does in one step: an in tile, an out tile, or one of each.
+// Everything in it is uniform over the wave except the lane's own pointers.
 template <typename V>
-struct LaneTile {
+struct Job {
     const V *src_i;
     V *dst_i;
     const V *src_o;
     V *dst_o;
+    uint32_t do_in, do_out;
+    uint32_t v0;  // this lane's first vector within the segment (range checks of ragged tiles)
 };
 
-template <typename V, bool IN, bool OUT>
-__device__ __forceinline__ LaneTile<V> lane_tile(const MoveParams &p, const int32_t *__restrict__ out_ids,
-                                                 const int32_t *__restrict__ out_slots,
-                                                 const int32_t *__restrict__ in_ids,
-                                                 const int32_t *__restrict__ in_slots, uint32_t t,
-                                                 uint32_t tile_vecs, uint32_t tid)
-{
-    LaneTile<V> r{nullptr, nullptr, nullptr, nullptr};
-    const uint32_t tile_bytes = tile_vecs * (uint32_t)sizeof(V);
-    if constexpr (IN) {
-        uint64_t ho, fo;
-        locate(p, p.in, in_ids, in_slots, t, p.far_slot_stride_in, p.far_plane_stride_in, tile_bytes, ho, fo);
-        r.src_i = reinterpret_cast<const V *>(p.far_in + fo) + tid;
-        r.dst_i = reinterpret_cast<V *>(p.hbm + ho) + tid;
-    }
-    if constexpr (OUT) {
-        uint64_t ho, fo;
-        locate(p, p.out, out_ids, out_slots, t, p.far_slot_stride_out, p.far_plane_stride_out, tile_bytes, ho, fo);
-        r.src_o = reinterpret_cast<const V *>(p.hbm + ho) + tid;
-        r.dst_o = reinterpret_cast<V *>(p.far_out + fo) + tid;
-    }
-    return r;
-}
-
-// Loads of one full tile: the far-side (host) loads first, they have the long
-// latency; then the HBM loads.  No lane predicate: all issue back to back.
-template <typename V, int U, bool IN, bool OUT>
-__device__ __forceinline__ void tile_loads(const LaneTile<V> &a, uint32_t lanes, V (&vi)[U], V (&vo)[U])
-{
-    if constexpr (IN) {
-#pragma unroll
-        for (int u = 0; u < U; u++) vi[u] = a.src_i[u * lanes];
-    }
-    if constexpr (OUT) {
-#pragma unroll
-        for (int u = 0; u < U; u++) vo[u] = a.src_o[u * lanes];
-    }
-}
-
-template <typename V, int U, bool IN, bool OUT>
-__device__ __forceinline__ void tile_stores(const LaneTile<V> &a, uint32_t lanes, const V (&vi)[U], const V (&vo)[U])
-{
-    if constexpr (OUT) {
-#pragma unroll
-        for (int u = 0; u < U; u++) a.dst_o[u * lanes] = vo[u];
-    }
-    if constexpr (IN) {
-#pragma unroll
-        for (int u = 0; u < U; u++) a.dst_i[u * lanes] = vi[u];
-    }
-}
-
-// Tiles t, t + stride, ... below t_end, all full, all with the same directions.
-// Software pipelined in registers: the loads of the workgroup's next tile are
-// issued before the stores of the current one, so each lane keeps up to 2 * U
-// vectors per direction in flight and the link sees no gap between a
-// workgroup's tiles.  Returns the first tile index >= t_end of this workgroup.
-template <typename V, int U, bool IN, bool OUT>
-__device__ __forceinline__ uint32_t run_full(const MoveParams &p, const int32_t *__restrict__ out_ids,
-                                             const int32_t *__restrict__ out_slots,
-                                             const int32_t *__restrict__ in_ids,
-                                             const int32_t *__restrict__ in_slots, uint32_t t, uint32_t t_end,
-                                             uint32_t stride, uint32_t lanes, uint32_t tid)
-{
-    if (t >= t_end) return t;
-    const uint32_t tile_vecs = lanes * U;
-    LaneTile<V> cur = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
-    V ai[U], ao[U];
-    tile_loads<V, U, IN, OUT>(cur, lanes, ai, ao);
-    for (t += stride; t < t_end; t += stride) {
-        const LaneTile<V> nxt = lane_tile<V, IN, OUT>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
-        V bi[U], bo[U];
-        tile_loads<V, U, IN, OUT>(nxt, lanes, bi, bo);
-        tile_stores<V, U, IN, OUT>(cur, lanes, ai, ao);
-        cur = nxt;
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            if constexpr (IN) ai[u] = bi[u];
-            if constexpr (OUT) ao[u] = bo[u];
-        }
-    }
-    tile_stores<V, U, IN, OUT>(cur, lanes, ai, ao);
-    return t;
-}
-
-// The in list is the longer one: its tiles t, t + stride, ... set the pace and
-// the out tiles are spread evenly over them, out tile s riding with the in tile
-// t at which floor(t * q / 2^32) steps from s to s + 1 (q = ceil(S * 2^32 / L),
-// so the steps are 0 or 1 and all S out tiles are met exactly once over the L
-// in tiles).  Measured on PCIe Gen5 x16: host->HBM reads can stay at the link's
+// Step t of a launch.  Normally step t is tile t of the out list and tile t of
+// the in list, as far as each list goes: while both last, every lane alternates
+// an out-vector with an in-vector, which locks the two link directions 1:1, and
+// the longer list's remainder then runs alone.
+//
+// With mix_q set the in list is the longer one: its tiles set the pace and the
+// out tiles are spread evenly over them, out tile s riding with the in tile t
+// at which floor(t * q / 2^32) steps from s to s + 1 (q = ceil(S * 2^32 / L), so
+// the steps are 0 or 1 and all S out tiles are met exactly once over the L in
+// tiles).  Measured on PCIe Gen5 x16: host->HBM reads can stay at the link's
 // one-way rate (55-57 GB/s) while up to ~0.85 as many bytes go the other way
 // (47 GB/s), 102 GB/s in all, whereas pairing the lists 1:1 and moving the rest
 // of the in list afterwards holds both at 49.5 GB/s for the paired part.  (The
 // mirror case gains nothing: with the out list longer, what limits is the
 // upstream direction, which carries the out data and the read requests of the
-// in data, and that sum does not depend on the order.)  Whether a tile has an
-// out tile riding along is uniform over the workgroup.
+// in data, and that sum does not depend on the order.)
 template <typename V, int U>
-__device__ __forceinline__ void run_in_heavy(const MoveParams &p, const int32_t *__restrict__ out_ids,
-                                             const int32_t *__restrict__ out_slots,
-                                             const int32_t *__restrict__ in_ids,
-                                             const int32_t *__restrict__ in_slots, uint32_t t, uint32_t stride,
-                                             uint32_t lanes, uint32_t tid)
+__device__ __forceinline__ Job<V> make_job(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                           const int32_t *__restrict__ out_slots,
+                                           const int32_t *__restrict__ in_ids,
+                                           const int32_t *__restrict__ in_slots, uint32_t t, uint32_t lane)
 {
-    const uint32_t tile_vecs = lanes * U, n_in = p.in.tiles, n_out = p.out.tiles;
-    for (; t < n_in; t += stride) {
+    constexpr uint32_t tile_vecs = kWave * U, tile_bytes = tile_vecs * (uint32_t)sizeof(V);
+    Job<V> j{nullptr, nullptr, nullptr, nullptr, 0u, 0u, 0u};
+    uint32_t t_out = t;
+    if (p.mix_q) {
         const uint64_t a = (uint64_t)t * p.mix_q, b = a + p.mix_q;
         const uint32_t s0 = (uint32_t)(a >> 32);
         uint32_t s1 = (uint32_t)(b >> 32);
-        s1 = s1 < n_out ? s1 : n_out;
-        const LaneTile<V> li = lane_tile<V, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
-        V vi[U], vo[U];
-        if (s1 > s0) {
-            const LaneTile<V> lo =
-                lane_tile<V, false, true>(p, out_ids, out_slots, in_ids, in_slots, s0, tile_vecs, tid);
-            tile_loads<V, U, true, false>(li, lanes, vi, vo);
-            tile_loads<V, U, false, true>(lo, lanes, vi, vo);
-            tile_stores<V, U, false, true>(lo, lanes, vi, vo);
-            tile_stores<V, U, true, false>(li, lanes, vi, vo);
-        } else {
-            tile_loads<V, U, true, false>(li, lanes, vi, vo);
-            tile_stores<V, U, true, false>(li, lanes, vi, vo);
+        s1 = s1 < p.out.tiles ? s1 : p.out.tiles;
+        j.do_in = 1u;
+        j.do_out = s1 > s0 ? 1u : 0u;
+        t_out = s0;
+    } else {
+        j.do_in = t < p.in.tiles ? 1u : 0u;
+        j.do_out = t < p.out.tiles ? 1u : 0u;
+    }
+    j.v0 = (t % p.tiles_per_seg) * tile_vecs + lane;
+    if (j.do_in) {
+        uint64_t ho, fo;
+        locate(p, p.in, in_ids, in_slots, t, p.far_slot_stride_in, p.far_plane_stride_in, tile_bytes, ho, fo);
+        j.src_i = reinterpret_cast<const V *>(p.far_in + fo) + lane;
+        j.dst_i = reinterpret_cast<V *>(p.hbm + ho) + lane;
+    }
+    if (j.do_out) {
+        uint64_t ho, fo;
+        locate(p, p.out, out_ids, out_slots, t_out, p.far_slot_stride_out, p.far_plane_stride_out, tile_bytes, ho,
+               fo);
+        j.src_o = reinterpret_cast<const V *>(p.hbm + ho) + lane;
+        j.dst_o = reinterpret_cast<V *>(p.far_out + fo) + lane;
+    }
+    return j;
+}
+
+// Loads of one job: the far-side (host) loads first, they have the long
+// latency; then the HBM loads.  Full tiles carry no lane predicate, so all
+// loads issue back to back.
+template <typename V, int U>
+__device__ __forceinline__ void job_loads(const MoveParams &p, const Job<V> &j, V (&vi)[U], V (&vo)[U])
+{
+    if (p.full_tiles) {
+        if (j.do_in) {
+#pragma unroll
+            for (int u = 0; u < U; u++) vi[u] = j.src_i[u * kWave];
+        }
+        if (j.do_out) {
+#pragma unroll
+            for (int u = 0; u < U; u++) vo[u] = j.src_o[u * kWave];
+        }
+    } else {
+        if (j.do_in) {
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (j.v0 + u * kWave < p.vec_per_seg) vi[u] = j.src_i[u * kWave];
+        }
+        if (j.do_out) {
+#pragma unroll
+            for (int u = 0; u < U; u++)
+                if (j.v0 + u * kWave < p.vec_per_seg) vo[u] = j.src_o[u * kWave];
         }
     }
 }
 
-// One tile with per-lane range checks: only for shapes whose segments are not
-// a whole number of tiles.
-template <typename V, int U>
-__device__ __forceinline__ void tile_ragged(const MoveParams &p, const int32_t *__restrict__ out_ids,
-                                            const int32_t *__restrict__ out_slots,
-                                            const int32_t *__restrict__ in_ids,
-                                            const int32_t *__restrict__ in_slots, uint32_t t, uint32_t lanes,
-                                            uint32_t tid)
+// Stores of one job.  LINK: the far side is host memory, and its stores are
+// marked non-temporal: plain stores linger in the write-back L2 and are only
+// pushed out when evicted or when the kernel ends, so the upstream link idles
+// early and a kernel's last megabytes leave while the downstream link idles
+// (measured, 8 + 8 MiB both ways: 237 us plain, 188 us non-temporal).
+template <typename V, int U, bool LINK>
+__device__ __forceinline__ void job_stores(const MoveParams &p, const Job<V> &j, const V (&vi)[U],
+                                           const V (&vo)[U])
 {
-    const uint32_t tile_vecs = lanes * U;
-    const bool do_in = t < p.in.tiles, do_out = t < p.out.tiles;
-    const uint32_t v0 = (t % p.tiles_per_seg) * tile_vecs + tid;
-    V vi[U], vo[U];
-    if (do_in) {
-        const LaneTile<V> a = lane_tile<V, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+    if (j.do_out) {
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) vi[u] = a.src_i[u * lanes];
-#pragma unroll
-        for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) a.dst_i[u * lanes] = vi[u];
+        for (int u = 0; u < U; u++) {
+            if (p.full_tiles || j.v0 + u * kWave < p.vec_per_seg) {
+                if constexpr (LINK) __builtin_nontemporal_store(vo[u], j.dst_o + u * kWave);
+                else j.dst_o[u * kWave] = vo[u];
+            }
+        }
     }
-    if (do_out) {
-        const LaneTile<V> a = lane_tile<V, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, tile_vecs, tid);
+    if (j.do_in) {
 #pragma unroll
         for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) vo[u] = a.src_o[u * lanes];
-#pragma unroll
-        for (int u = 0; u < U; u++)
-            if (v0 + u * lanes < p.vec_per_seg) a.dst_o[u * lanes] = vo[u];
+            if (p.full_tiles || j.v0 + u * kWave < p.vec_per_seg) j.dst_i[u * kWave] = vi[u];
     }
 }
 
 // V: vector moved per lane (16 bytes when the segment allows it).
-// U: vectors per lane per tile; a tile is blockDim.x * U consecutive vectors of
-//    one segment, so every wave touches 64 * sizeof(V) contiguous bytes per
-//    access on both sides (full 1 KiB rows at V = 16 bytes).
-// Workgroup g takes tiles g, g + G, ... .  Tile index t means tile t of the out
-// list and tile t of the in list: while both lists last, every lane alternates
-// an out-vector with an in-vector, which locks the two link directions 1:1;
-// the longer list's remainder then runs alone.  Lists may be empty.  With
-// mix_q set (in list longer, full tiles) the out tiles are instead spread over
-// the whole in list.
-template <typename V, int U>
+// U: vectors per lane per tile; a tile is 64 * U consecutive vectors of one
+//    segment, so every wave access touches 64 * sizeof(V) contiguous bytes on
+//    both sides (full 1 KiB rows at V = 16 bytes).
+// A wave handles one job at a time: its loads, then its stores.  The addresses
+// of the wave's next job (two divisions, the scalar loads of id and slot) are
+// worked out while the loads of the current one are in flight.  What keeps the
+// link busy is the number of waves, not depth per wave.
+//
+// Which tile a wave takes next: with p.claim the waves draw tile indices from a
+// counter (the draw for the job after next is issued before the current job's
+// loads, so its latency is never waited for).  With a fixed share per wave the
+// waves of a link-bound launch drift apart by several per cent and the launch
+// ends with a tail of ~100 us in which too few waves are left to fill the link;
+// drawn tiles end within one tile of each other, and the rate no longer
+// depends on how the wave count divides the tile count.  The last wave to
+// finish puts both counters back to zero for the next launch on the stream.
+// HBM-bound launches (pack / unpack) move a tile in ~2 ns chip-wide, too fast
+// for one counter, and use the fixed share.
+template <typename V, int U, bool LINK>
 __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p,
                                                               const int32_t *__restrict__ out_ids,
                                                               const int32_t *__restrict__ out_slots,
                                                               const int32_t *__restrict__ in_ids,
                                                               const int32_t *__restrict__ in_slots)
 {
-    const uint32_t tid = threadIdx.x, lanes = blockDim.x, stride = gridDim.x;
-    const uint32_t n_both = p.out.tiles < p.in.tiles ? p.out.tiles : p.in.tiles;
-    const uint32_t n_all = p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles;
-    uint32_t t = blockIdx.x;
-    if (!p.full_tiles) {
-        for (; t < n_all; t += stride) tile_ragged<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lanes, tid);
+    const uint32_t lane = threadIdx.x & (kWave - 1u), waves_per_wg = blockDim.x / kWave;
+    const uint32_t wave = blockIdx.x * waves_per_wg + threadIdx.x / kWave, n_waves = gridDim.x * waves_per_wg;
+    const uint32_t n_steps = p.mix_q ? p.in.tiles : (p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles);
+    V vi[U], vo[U];
+    if (!p.claim) {
+        uint32_t t = wave;
+        if (t >= n_steps) return;
+        Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
+        for (;;) {
+            job_loads<V, U>(p, cur, vi, vo);
+            t += n_waves;
+            const bool more = t < n_steps;
+            Job<V> nxt = cur;
+            if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
+            job_stores<V, U, LINK>(p, cur, vi, vo);
+            if (!more) break;
+            cur = nxt;
+        }
         return;
     }
-    if (p.mix_q) {
-        run_in_heavy<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, stride, lanes, tid);
-        return;
+    // drawn tiles: t0 is the current step, t1 the next, the draw in flight the one after
+    uint32_t d0 = 0, d1 = 0;
+    if (lane == 0) {
+        d0 = atomicAdd(&p.claim[0], 1u);
+        d1 = atomicAdd(&p.claim[0], 1u);
     }
-    t = run_full<V, U, true, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_both, stride, lanes, tid);
-    if (p.out.tiles > p.in.tiles)
-        run_full<V, U, false, true>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
-    else
-        run_full<V, U, true, false>(p, out_ids, out_slots, in_ids, in_slots, t, n_all, stride, lanes, tid);
+    const uint32_t t0 = __builtin_amdgcn_readfirstlane(d0);
+    uint32_t t1 = __builtin_amdgcn_readfirstlane(d1);
+    if (t0 < n_steps) {
+        Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t0, lane);
+        for (;;) {
+            const bool more = t1 < n_steps;
+            uint32_t d2 = 0;
+            if (more && lane == 0) d2 = atomicAdd(&p.claim[0], 1u);
+            job_loads<V, U>(p, cur, vi, vo);
+            Job<V> nxt = cur;
+            if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t1, lane);
+            job_stores<V, U, LINK>(p, cur, vi, vo);
+            if (!more) break;
+            cur = nxt;
+            t1 = __builtin_amdgcn_readfirstlane(d2);
+        }
+    }
+    // Every draw this wave issued has been read back above, so the counter holds
+    // all of its increments before the wave reports itself done; the wave that
+    // sees every other one done can therefore put the counters back.
+    if (lane == 0 && atomicAdd(&p.claim[1], 1u) == n_waves - 1u) {
+        p.claim[0] = 0u;
+        p.claim[1] = 0u;
+    }
 }
 
 // Synthetic decode reader: streams every segment of the named blocks, plane by
