@@ -18,6 +18,11 @@ HIPCC_FLAGS = [
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The tile draws of the move kernel are one atomic per wave whose result is
+    # wanted a whole step later.  The compiler's atomic optimizer would rewrite
+    # each into "one lane adds for all active lanes, then broadcast", and the
+    # broadcast waits for the atomic (and every access before it) on the spot.
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

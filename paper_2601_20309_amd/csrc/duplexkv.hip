@@ -294,32 +294,29 @@ int link_u(const kv_engine *e)
     return e->cfg.vecs_per_lane ? e->cfg.vecs_per_lane : 1;
 }
 
-// Launch shape of a link-bound kernel.  What saturates PCIe Gen5 x16 is bytes
-// in flight, not workgroups, and what a kernel running beside the copy loses
-// grows with those same bytes, so the default is the smallest shape on the
-// plateau (all measured, 256 + 256 MiB of scattered 2 MiB blocks):
-//  - both directions in one launch: 124 one-wave workgroups.  Each lane keeps
-//    two 16-byte vectors per direction in flight (the loop is pipelined one
-//    tile deep): 248 KiB each way.  98.6 GB/s; 96 x 256 lanes gives 97.0 and
-//    takes a co-running HBM-bound reader from 6.3 to 3.9 TB/s instead of 5.3.
-//    Counts that are multiples of 8, the number of XCDs workgroups are dealt
-//    over, are 2 % slower at this size (120: 96.7, 124: 98.6, 128: 96.7), and
-//    between 136 and 200 waves the rate dips to 90-93 GB/s, so the count is
-//    not rounded.
-//  - one direction alone has half the accesses per lane: 64 x 256 lanes
-//    (57.3 GB/s in, 55.4 out, both the link's one-way rate).
+// Launch shape of a link-bound kernel.  Waves are the workers, each with one
+// tile (1 KiB per direction at 16-byte vectors) in flight; workgroups only pack
+// them.  What saturates PCIe Gen5 x16 is bytes in flight, and what a kernel
+// running beside the copy loses grows with those same bytes, so the default is
+// the low end of the plateau.  Measured, scattered 2 MiB blocks, both directions
+// in one launch (GB/s at 256 + 256 MiB alone / at 4 + 4 GiB beside an HBM-bound
+// reader, and what the reader keeps of its 6.5 TB/s):
+//    64 waves  84.4 /  68.2 (5.75)     112 waves 100.1 / 100.0 (5.30)
+//    80 waves  96.5 /  83.5 (5.61)     124 waves 100.2 / 100.5 (5.14)
+//    96 waves  99.5 /  96.5 (5.47)     144 waves 100.1 / 100.6 (4.95)
+//   104 waves  99.9 /  99.4 (5.39)     192 waves 100.1 / 100.7 (4.50)
+// The same waves packed four to a workgroup (31 x 256 lanes) do slightly worse
+// beside the reader (97.8), so the default is one wave per workgroup, spread
+// over as many CUs.  One direction alone reaches the link's one-way rate with
+// the same shape (55.9 GB/s out, 57.3 in).
 // max_copy_wgs counts workgroups of wg_lanes lanes; set alone it keeps 256-lane
-// workgroups, wg_lanes set alone keeps the total number of lanes.
-void link_shape(const kv_engine *e, bool both_in_one_launch, int &wgs, int &lanes)
+// workgroups, wg_lanes set alone keeps the number of waves.
+void link_shape(const kv_engine *e, int &wgs, int &lanes)
 {
+    constexpr int kWaves = 112;
     const int cw = e->cfg.max_copy_wgs, cl = e->cfg.wg_lanes;
-    if (both_in_one_launch) {
-        lanes = cl ? cl : (cw ? dkv::kThreads : 64);
-        wgs = cw ? cw : std::max(1, 124 * 64 / lanes);
-    } else {
-        lanes = cl ? cl : dkv::kThreads;
-        wgs = cw ? cw : std::max(1, 64 * dkv::kThreads / lanes);
-    }
+    lanes = cl ? cl : (cw ? dkv::kThreads : dkv::kWave);
+    wgs = cw ? cw : std::max(1, kWaves * dkv::kWave / lanes);
 }
 
 // HBM-bound pack / unpack launches want the whole chip.
@@ -336,8 +333,8 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
     const int u = link_u(e);
     const bool fused = path == KV_PATH_FUSED && no > 0 && ni > 0;
-    int wgs1 = 0, lanes1 = 0;  // shape of a launch that carries one direction
-    link_shape(e, false, wgs1, lanes1);
+    int wgs1 = 0, lanes1 = 0;
+    link_shape(e, wgs1, lanes1);
     auto params = [&](unsigned int *claim) {
         MoveParams q = base_params(e, u);
         q.claim = claim;
@@ -377,8 +374,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     if (fused) {
         // one launch on stream_out carries both directions; stream_in is joined
         // before (if it holds work) and after
-        int wgs2 = 0, lanes2 = 0;
-        link_shape(e, true, wgs2, lanes2);
+        const int wgs2 = wgs1, lanes2 = lanes1;
         MoveParams p = params(e->claim);
         if (!desc(p, no, p.out) || !desc(p, ni, p.in)) return KV_EUNSUP;
         // in list longer: spread the out tiles over it instead of pairing 1:1
@@ -916,7 +912,8 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
         return fail(KV_ENOMEM);
     }
     // the tile counters start at zero; every launch leaves them at zero again
-    if (hipMemset(e->claim, 0, 2 * kClaimStride * sizeof(unsigned int)) != hipSuccess) return fail(KV_EHIP);
+    if (hipMemset(e->claim, 0, 2 * kClaimStride * sizeof(unsigned int)) != hipSuccess)
+        return fail(KV_EHIP);
     bool ok = true;
     for (int k = 0; k < kRing; k++) {
         ok = ok && hipEventCreate(&e->ring_out[k]) == hipSuccess;
@@ -1126,8 +1123,14 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
         HIPTRY(e, hipMemcpyAsync(e->read_ids, e->read_ids_host, (size_t)n * sizeof(int32_t),
                                  hipMemcpyHostToDevice, e->s_read));
     }
-    // 8 workgroups of 256 lanes fill a CU; more only queue (measured: 6.26 TB/s at 8 per CU, 6.15 at 16)
-    int wgs = 8 * (e->n_cus > 0 ? e->n_cus : 256);
+    // Six of these workgroups fill a CU's registers.  Measured per pass over 37.5 GiB:
+    // 4 per CU 5.74 TB/s, 5 per CU 6.40, 5.5 per CU 6.51, 6 and more 6.45 (the
+    // surplus only queues).  From 6 per CU on the persistent workgroups also hold
+    // every register of the chip for a whole pass (~6 ms), so that no other
+    // kernel's waves can start before the pass ends, which no model execution made
+    // of many short kernels would do to a rotation; 5.5 per CU is the fastest and
+    // leaves that room.
+    int wgs = 11 * (e->n_cus > 0 ? e->n_cus : 256) / 2;
     if (max_wgs > 0) wgs = std::min(wgs, (int)max_wgs);
     wgs = (int)std::min<uint32_t>((uint32_t)wgs, std::max<uint32_t>(p.tiles, 1u));
     HIPTRY(e, hipEventRecord(e->read_ev[0], e->s_read));

@@ -53,7 +53,8 @@ struct kv_engine {
     // descriptor ring: per set [out_ids | out_slots | in_ids | in_slots]
     int32_t *desc_host = nullptr, *desc_dev = nullptr;
     size_t desc_cap = 0;  // ints per set
-    unsigned int *claim = nullptr;  // device: [0..1] for stream_out's launches, [kClaimStride..+1] for stream_in's
+    // device: [0..1] counters of stream_out's launches, [kClaimStride..+1] of stream_in's
+    unsigned int *claim = nullptr;
     // ring_out[k] / ring_in[k] are recorded after the last work that reads set k
     // on each stream; they double as the end-of-work timestamps for the stats
     hipEvent_t ring_out[dkv::kRing] = {}, ring_in[dkv::kRing] = {};

@@ -20,6 +20,9 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;          // a wave is the unit of work: one tile at a time
 constexpr int kThreads = 256;      // default lanes per workgroup (4 waves)
+#ifndef DKV_DRAW_CHUNK
+#define DKV_DRAW_CHUNK 4
+#endif
 constexpr int kMaxThreads = 1024;  // workgroups only pack waves; any multiple of 64 up to this
 
 // One direction's block list as the kernel sees it.  The id arrays themselves
@@ -59,6 +62,7 @@ struct MoveParams {
     unsigned int *claim;
     DirDesc out, in;
 };
+
 
 // Tile t of direction d -> byte offsets (segment base + tile start) on both sides.
 __device__ __forceinline__ void locate(const MoveParams &p, const DirDesc &d,
@@ -151,31 +155,20 @@ __device__ __forceinline__ Job<V> make_job(const MoveParams &p, const int32_t *_
 }
 
 // Loads of one job: the far-side (host) loads first, they have the long
-// latency; then the HBM loads.  Full tiles carry no lane predicate, so all
-// loads issue back to back.
-template <typename V, int U>
+// latency; then the HBM loads.  FULL: the segment is a whole number of tiles, no
+// lane is ever out of range, and all loads issue back to back.
+template <typename V, int U, bool FULL>
 __device__ __forceinline__ void job_loads(const MoveParams &p, const Job<V> &j, V (&vi)[U], V (&vo)[U])
 {
-    if (p.full_tiles) {
-        if (j.do_in) {
+    if (j.do_in) {
 #pragma unroll
-            for (int u = 0; u < U; u++) vi[u] = j.src_i[u * kWave];
-        }
-        if (j.do_out) {
+        for (int u = 0; u < U; u++)
+            if (FULL || j.v0 + u * kWave < p.vec_per_seg) vi[u] = j.src_i[u * kWave];
+    }
+    if (j.do_out) {
 #pragma unroll
-            for (int u = 0; u < U; u++) vo[u] = j.src_o[u * kWave];
-        }
-    } else {
-        if (j.do_in) {
-#pragma unroll
-            for (int u = 0; u < U; u++)
-                if (j.v0 + u * kWave < p.vec_per_seg) vi[u] = j.src_i[u * kWave];
-        }
-        if (j.do_out) {
-#pragma unroll
-            for (int u = 0; u < U; u++)
-                if (j.v0 + u * kWave < p.vec_per_seg) vo[u] = j.src_o[u * kWave];
-        }
+        for (int u = 0; u < U; u++)
+            if (FULL || j.v0 + u * kWave < p.vec_per_seg) vo[u] = j.src_o[u * kWave];
     }
 }
 
@@ -184,14 +177,14 @@ __device__ __forceinline__ void job_loads(const MoveParams &p, const Job<V> &j, 
 // pushed out when evicted or when the kernel ends, so the upstream link idles
 // early and a kernel's last megabytes leave while the downstream link idles
 // (measured, 8 + 8 MiB both ways: 237 us plain, 188 us non-temporal).
-template <typename V, int U, bool LINK>
+template <typename V, int U, bool LINK, bool FULL>
 __device__ __forceinline__ void job_stores(const MoveParams &p, const Job<V> &j, const V (&vi)[U],
                                            const V (&vo)[U])
 {
     if (j.do_out) {
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            if (p.full_tiles || j.v0 + u * kWave < p.vec_per_seg) {
+            if (FULL || j.v0 + u * kWave < p.vec_per_seg) {
                 if constexpr (LINK) __builtin_nontemporal_store(vo[u], j.dst_o + u * kWave);
                 else j.dst_o[u * kWave] = vo[u];
             }
@@ -200,29 +193,127 @@ __device__ __forceinline__ void job_stores(const MoveParams &p, const Job<V> &j,
     if (j.do_in) {
 #pragma unroll
         for (int u = 0; u < U; u++)
-            if (p.full_tiles || j.v0 + u * kWave < p.vec_per_seg) j.dst_i[u * kWave] = vi[u];
+            if (FULL || j.v0 + u * kWave < p.vec_per_seg) j.dst_i[u * kWave] = vi[u];
     }
+}
+
+// One draw of `n` consecutive steps from the counter by the wave's first lane
+// (the others get 0).  The value comes back a memory latency later; drawn()
+// reads it.
+__device__ __forceinline__ uint32_t draw(const MoveParams &p, uint32_t lane, uint32_t n)
+{
+    uint32_t d = 0;
+    if (lane == 0) d = atomicAdd(&p.claim[0], n);
+    return d;
+}
+
+// The drawn value, wave-uniform.  The empty asm pins the first use of the
+// register to this point of the program: without it the compiler is free to
+// read the value (and so to wait for the atomic and for every vector memory
+// access issued before it) right behind the draw.
+__device__ __forceinline__ uint32_t drawn(uint32_t d)
+{
+    asm volatile("" : "+v"(d));
+    return __builtin_amdgcn_readfirstlane(d);
+}
+
+// Fixed share: wave w of W takes steps w, w + W, ...
+template <typename V, int U, bool LINK, bool FULL>
+__device__ __forceinline__ void run_fixed(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                          const int32_t *__restrict__ out_slots,
+                                          const int32_t *__restrict__ in_ids,
+                                          const int32_t *__restrict__ in_slots, uint32_t n_steps, uint32_t wave,
+                                          uint32_t n_waves, uint32_t lane)
+{
+    uint32_t t = wave;
+    if (t >= n_steps) return;
+    V vi[U], vo[U];
+    Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
+    for (;;) {
+        job_loads<V, U, FULL>(p, cur, vi, vo);
+        t += n_waves;
+        const bool more = t < n_steps;
+        Job<V> nxt = cur;
+        if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
+        job_stores<V, U, LINK, FULL>(p, cur, vi, vo);
+        if (!more) break;
+        cur = nxt;
+    }
+}
+
+// Drawn steps.  A draw takes kDrawChunk consecutive steps (one atomic per step
+// would be ~50 M a second on one address, which beside an HBM-bound kernel is
+// what limits the launch: 93 GB/s whatever the number of waves), except near the
+// end, where steps are drawn singly so that the waves still finish within one
+// step of each other.  The draw for the next chunk is issued when the current
+// chunk starts and read when it ends.  Every draw the wave issues is read back
+// before the function returns.
+constexpr uint32_t kDrawChunk = DKV_DRAW_CHUNK;
+
+template <typename V, int U, bool LINK, bool FULL>
+__device__ __forceinline__ void run_drawn(const MoveParams &p, const int32_t *__restrict__ out_ids,
+                                          const int32_t *__restrict__ out_slots,
+                                          const int32_t *__restrict__ in_ids,
+                                          const int32_t *__restrict__ in_slots, uint32_t n_steps, uint32_t n_waves,
+                                          uint32_t lane)
+{
+    // steps at or beyond `single` are drawn one at a time
+    const uint32_t tail = 2u * kDrawChunk * n_waves, single = n_steps > tail ? n_steps - tail : 0u;
+    uint32_t c = single ? kDrawChunk : 1u;
+    uint32_t t = drawn(draw(p, lane, c));  // current step
+    uint32_t e = t + c;                    // end of the chunk it belongs to
+    uint32_t cn = t < single ? kDrawChunk : 1u;
+    uint32_t d = draw(p, lane, cn);        // the next chunk, in flight
+    if (t < n_steps) {
+        V vi[U], vo[U];
+        Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
+        for (;;) {
+            job_loads<V, U, FULL>(p, cur, vi, vo);
+            // The next step.  At the end of a chunk the pending draw is read: here,
+            // where the loads have to be waited for anyway (the draw is older than
+            // they are), and before the stores: the vector memory counter retires in
+            // order, so reading it behind the stores would wait for them, and a wave
+            // would then pay store latency and load latency in turn.  As it is, a
+            // step's stores have the whole next step to retire.
+            uint32_t tn = t + 1u;
+            if (tn >= e) {
+                tn = drawn(d);
+                e = tn + cn;
+                cn = tn < single ? kDrawChunk : 1u;
+                d = draw(p, lane, cn);
+            }
+            const bool more = tn < n_steps;
+            Job<V> nxt = cur;
+            if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, tn, lane);
+            job_stores<V, U, LINK, FULL>(p, cur, vi, vo);
+            if (!more) break;
+            cur = nxt;
+            t = tn;
+        }
+    }
+    (void)drawn(d);
 }
 
 // V: vector moved per lane (16 bytes when the segment allows it).
 // U: vectors per lane per tile; a tile is 64 * U consecutive vectors of one
 //    segment, so every wave access touches 64 * sizeof(V) contiguous bytes on
 //    both sides (full 1 KiB rows at V = 16 bytes).
-// A wave handles one job at a time: its loads, then its stores.  The addresses
-// of the wave's next job (two divisions, the scalar loads of id and slot) are
-// worked out while the loads of the current one are in flight.  What keeps the
-// link busy is the number of waves, not depth per wave.
+// LINK: the far side is host memory.
+// A wave is the unit of work: it takes a step, issues its loads, works out the
+// addresses of its next step (two divisions, the scalar loads of id and slot)
+// while they are in flight, and stores.  What keeps the link busy is the number
+// of waves: a second step in flight per wave buys what a second wave buys.
 //
-// Which tile a wave takes next: with p.claim the waves draw tile indices from a
-// counter (the draw for the job after next is issued before the current job's
-// loads, so its latency is never waited for).  With a fixed share per wave the
-// waves of a link-bound launch drift apart by several per cent and the launch
-// ends with a tail of ~100 us in which too few waves are left to fill the link;
-// drawn tiles end within one tile of each other, and the rate no longer
-// depends on how the wave count divides the tile count.  The last wave to
-// finish puts both counters back to zero for the next launch on the stream.
-// HBM-bound launches (pack / unpack) move a tile in ~2 ns chip-wide, too fast
-// for one counter, and use the fixed share.
+// Which step a wave takes next: with p.claim the waves draw step indices from a
+// counter (the draw for the step after next is issued a whole step ahead, so
+// its latency is never waited for).  With a fixed share per wave the waves of a
+// link-bound launch drift apart by several per cent and the launch ends with a
+// tail of ~100 us in which too few waves are left to fill the link; drawn steps
+// end within one tile of each other, and the rate no longer depends on how the
+// wave count divides the tile count.  The last wave to finish puts both
+// counters back to zero for the next launch on the stream.  HBM-bound launches
+// (pack / unpack) move a tile in ~2 ns chip-wide, too fast for one counter, and
+// use the fixed share.
 template <typename V, int U, bool LINK>
 __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p,
                                                               const int32_t *__restrict__ out_ids,
@@ -233,49 +324,20 @@ __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p
     const uint32_t lane = threadIdx.x & (kWave - 1u), waves_per_wg = blockDim.x / kWave;
     const uint32_t wave = blockIdx.x * waves_per_wg + threadIdx.x / kWave, n_waves = gridDim.x * waves_per_wg;
     const uint32_t n_steps = p.mix_q ? p.in.tiles : (p.out.tiles > p.in.tiles ? p.out.tiles : p.in.tiles);
-    V vi[U], vo[U];
     if (!p.claim) {
-        uint32_t t = wave;
-        if (t >= n_steps) return;
-        Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
-        for (;;) {
-            job_loads<V, U>(p, cur, vi, vo);
-            t += n_waves;
-            const bool more = t < n_steps;
-            Job<V> nxt = cur;
-            if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
-            job_stores<V, U, LINK>(p, cur, vi, vo);
-            if (!more) break;
-            cur = nxt;
-        }
+        if (p.full_tiles)
+            run_fixed<V, U, LINK, true>(p, out_ids, out_slots, in_ids, in_slots, n_steps, wave, n_waves, lane);
+        else
+            run_fixed<V, U, LINK, false>(p, out_ids, out_slots, in_ids, in_slots, n_steps, wave, n_waves, lane);
         return;
     }
-    // drawn tiles: t0 is the current step, t1 the next, the draw in flight the one after
-    uint32_t d0 = 0, d1 = 0;
-    if (lane == 0) {
-        d0 = atomicAdd(&p.claim[0], 1u);
-        d1 = atomicAdd(&p.claim[0], 1u);
-    }
-    const uint32_t t0 = __builtin_amdgcn_readfirstlane(d0);
-    uint32_t t1 = __builtin_amdgcn_readfirstlane(d1);
-    if (t0 < n_steps) {
-        Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t0, lane);
-        for (;;) {
-            const bool more = t1 < n_steps;
-            uint32_t d2 = 0;
-            if (more && lane == 0) d2 = atomicAdd(&p.claim[0], 1u);
-            job_loads<V, U>(p, cur, vi, vo);
-            Job<V> nxt = cur;
-            if (more) nxt = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t1, lane);
-            job_stores<V, U, LINK>(p, cur, vi, vo);
-            if (!more) break;
-            cur = nxt;
-            t1 = __builtin_amdgcn_readfirstlane(d2);
-        }
-    }
-    // Every draw this wave issued has been read back above, so the counter holds
-    // all of its increments before the wave reports itself done; the wave that
-    // sees every other one done can therefore put the counters back.
+    if (p.full_tiles)
+        run_drawn<V, U, LINK, true>(p, out_ids, out_slots, in_ids, in_slots, n_steps, n_waves, lane);
+    else
+        run_drawn<V, U, LINK, false>(p, out_ids, out_slots, in_ids, in_slots, n_steps, n_waves, lane);
+    // Every draw this wave issued has been read back, so the counter holds all of
+    // its increments before the wave reports itself done; the wave that sees
+    // every other one done can therefore put the counters back.
     if (lane == 0 && atomicAdd(&p.claim[1], 1u) == n_waves - 1u) {
         p.claim[0] = 0u;
         p.claim[1] = 0u;
