@@ -347,9 +347,10 @@ def interference():
     print("| rotation path | copy WGs x lanes | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
           "reader alone TB/s | reader beside rotation TB/s |")
     print("|---|---|---|---|---|---|")
-    for path, wgs, lanes, contiguous in [(B.KV_PATH_FUSED, 0, 0, False), (B.KV_PATH_FUSED, 96, 256, False),
-                                         (B.KV_PATH_FUSED, 100, 64, False), (B.KV_PATH_FUSED, 31, 256, False),
-                                         (B.KV_PATH_FUSED, 25, 256, False), (B.KV_PATH_FUSED, 16, 256, False),
+    for path, wgs, lanes, contiguous in [(B.KV_PATH_FUSED, 0, 0, False), (B.KV_PATH_FUSED, 192, 64, False),
+                                         (B.KV_PATH_FUSED, 144, 64, False), (B.KV_PATH_FUSED, 96, 64, False),
+                                         (B.KV_PATH_FUSED, 80, 64, False), (B.KV_PATH_FUSED, 64, 64, False),
+                                         (B.KV_PATH_FUSED, 28, 256, False),
                                          (B.KV_PATH_SDMA_STAGED, 0, 0, True), (B.KV_PATH_DMA_BLOCKS, 0, 0, False)]:
         rot = W.config_rotation(name, contiguous_slots=contiguous)
         named = np.zeros(shape.n_hbm_blocks, bool)
@@ -395,7 +396,7 @@ def interference():
                 read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
         ms_both = statistics.median(both)
         launch = ("no kernel, block-first cache" if path == B.KV_PATH_DMA_BLOCKS else "pack / unpack kernels"
-                  if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (124 x 64)")
+                  if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (112 x 64)")
         print(f"| {B.PATH_NAMES[path]} | {launch} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
               f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
         eng.kv_destroy()
