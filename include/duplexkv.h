@@ -82,8 +82,8 @@ typedef struct {
     int32_t chunk_layers;  /* layers per pipeline chunk; 0 = engine picks */
     int32_t max_copy_wgs;  /* workgroups (of wg_lanes lanes; of 256 if wg_lanes is 0) a copy kernel may occupy; 0 = engine picks */
     int32_t vecs_per_lane; /* 16-byte vectors each lane keeps in flight per direction in the link kernels: 0 = engine picks, else 1, 2, 4 or 8 */
-    int32_t wg_lanes;      /* lanes per workgroup of the link kernels: 0 = engine picks (with max_copy_wgs also 0: 124 x 64 for both
-                              directions in one launch, 64 x 256 for one), else a multiple of 64 up to 1024 */
+    int32_t wg_lanes;      /* lanes per workgroup of the link kernels (workgroups only pack waves; a wave is the unit of work):
+                              0 = engine picks (with max_copy_wgs also 0: 112 one-wave workgroups), else a multiple of 64 up to 1024 */
     int32_t hbm_layout;    /* KV_HBM_* */
     uint64_t staging_bytes;/* SDMA_STAGED: bytes of HBM staging per direction = largest chunk; 0 = engine picks (256 MiB) */
 } kv_config;

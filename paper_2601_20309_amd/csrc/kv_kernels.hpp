@@ -19,10 +19,7 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kWave = 64;          // a wave is the unit of work: one tile at a time
-constexpr int kThreads = 256;      // default lanes per workgroup (4 waves)
-#ifndef DKV_DRAW_CHUNK
-#define DKV_DRAW_CHUNK 4
-#endif
+constexpr int kThreads = 256;      // lanes per workgroup of the HBM-bound launches and of the reader (4 waves)
 constexpr int kMaxThreads = 1024;  // workgroups only pack waves; any multiple of 64 up to this
 
 // One direction's block list as the kernel sees it.  The id arrays themselves
@@ -248,7 +245,7 @@ __device__ __forceinline__ void run_fixed(const MoveParams &p, const int32_t *__
 // step of each other.  The draw for the next chunk is issued when the current
 // chunk starts and read when it ends.  Every draw the wave issues is read back
 // before the function returns.
-constexpr uint32_t kDrawChunk = DKV_DRAW_CHUNK;
+constexpr uint32_t kDrawChunk = 4;
 
 template <typename V, int U, bool LINK, bool FULL>
 __device__ __forceinline__ void run_drawn(const MoveParams &p, const int32_t *__restrict__ out_ids,
