@@ -48,8 +48,10 @@ def test_batch_rotation_full_size():
     case.stage(rot.in_slots)
     case.rotate(rot)
     case.check()
-    # undo, then redo request pair by request pair
+    # undo (the in list is now the longer one: out tiles spread over the in tiles), then redo
+    # request pair by request pair
     case.rotate(rot.inverse())
+    case.check()
     bo, bi = info["bounds_out"], info["bounds_in"]
     for r in range(len(bo) - 1):
         case.rotate(W.Rotation(rot.out_ids[bo[r]:bo[r + 1]], rot.out_slots[bo[r]:bo[r + 1]],
