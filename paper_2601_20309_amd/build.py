@@ -49,5 +49,23 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(ROOT, "examples", "duplex_demo.c")
+EXAMPLE_BIN = os.path.join(ROOT, "examples", "duplex_demo")
+
+
+def build_example(out: str = EXAMPLE_BIN) -> str:
+    """The plain-C example against the built library: a C compiler, the public
+    header and the HIP runtime's C API are all it needs."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-O2", "-Wall", "-Wextra", "-Werror", EXAMPLE_SRC, "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(rocm, "include"), "-L", os.path.dirname(LIB), "-lduplexkv",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../paper_2601_20309_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", out]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building the C example failed:\n" + r.stderr)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, verbose=True))
