@@ -49,6 +49,7 @@ extern "C" {
 #define KV_EHIP     (-6)  /* HIP runtime failure (no device, launch or copy error); sticky */
 #define KV_EUNSUP   (-7)  /* the chosen path cannot serve this shape or request */
 #define KV_ENOSPC   (-8)  /* block table: not enough free HBM blocks or host slots */
+#define KV_EBUSY    (-9)  /* a block or slot is still used the other way round by an un-waited call on the other stream */
 
 /* ---- host pool layouts ---- */
 #define KV_HOST_BLOCK_FIRST 0
@@ -153,9 +154,14 @@ int kv_swap_in(kv_engine *engine, const int32_t *host_slots, const int32_t *bloc
  * one call, running at the same time.  Admission as in kv_validate().  After
  * the call returns, later work on stream_out is ordered after the out copies
  * and later work on stream_in after the in copies.  Two calls that have not
- * been separated by kv_wait() run in enqueue order per stream; naming a block
- * or slot that an un-waited call still uses in the other direction is a caller
- * error.
+ * been separated by kv_wait() run in enqueue order per stream, and the two
+ * streams run side by side.  A call that would read a block or slot which an
+ * un-waited call on the other stream writes, or write one which such a call
+ * reads, is refused with KV_EBUSY and enqueues nothing (kv_swap_out / kv_swap_in
+ * likewise).  A rotation that runs as one launch for both directions (the
+ * default path with both lists non-empty) is ordered after everything enqueued
+ * before it and before everything enqueued after it, so such rotations can
+ * follow one another, over the same blocks too, without a wait.
  */
 int kv_rotate(kv_engine *engine,
               const int32_t *out_block_ids, const int32_t *out_host_slots, int32_t n_out,

@@ -16,8 +16,8 @@ import torch  # noqa: F401
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduplexkv.so")
 
-KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP, KV_ENOSPC = \
-    0, -1, -2, -3, -4, -5, -6, -7, -8
+KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP, KV_ENOSPC, KV_EBUSY = \
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9
 KV_BLOCK_DIRTY, KV_BLOCK_FULL, KV_BLOCK_SYNCED, KV_BLOCK_HOST = 1, 2, 3, 4
 KV_HOST_BLOCK_FIRST, KV_HOST_LAYER_FIRST = 0, 1
 KV_HBM_LAYER_FIRST, KV_HBM_BLOCK_FIRST = 0, 1

@@ -736,6 +736,11 @@ int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, con
     if (no == 0 && ni == 0) return KV_OK;
     int path = e->cfg.path;
     if (path == KV_PATH_AUTO) path = (no > 0 && ni > 0) ? KV_PATH_FUSED : KV_PATH_ZEROCOPY;
+    // The block table orders its own calls across the two streams; for everyone
+    // else a call that would race with un-waited work on the other stream is
+    // refused.  One launch for both directions joins the streams instead.
+    const bool joins = path == KV_PATH_FUSED && no > 0 && ni > 0;
+    if (!e->in_after_out && !joins && e->hazards.races(oi, os, no, ii, is, ni)) return KV_EBUSY;
     if (path == KV_PATH_SDMA_STAGED) {
         rc = ensure_staging(e);
         if (rc != KV_OK) return rc;
@@ -766,6 +771,8 @@ int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, con
         }
     }
     if (rc != KV_OK) return rc;
+    if (joins) e->hazards.join();
+    else e->hazards.stamp(oi, os, no, ii, is, ni);
     e->acc.bytes_out += (uint64_t)no * e->block_bytes;
     e->acc.bytes_in += (uint64_t)ni * e->block_bytes;
     e->acc.path_used = path;
@@ -931,6 +938,7 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
     ok = ok && hipEventCreateWithFlags(&e->ev_join, hipEventDisableTiming) == hipSuccess;
     if (!ok) return fail(KV_EHIP);
     e->marks.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
+    e->hazards.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
     if (cfg->path == KV_PATH_SDMA_STAGED) {
         rc = ensure_staging(e);
         if (rc != KV_OK) return fail(rc);
@@ -976,6 +984,7 @@ int kv_wait(kv_engine *e)
         HIPTRY(e, hipStreamSynchronize(side == 0 ? e->s_out : e->s_in));
     }
     e->out_pending = e->in_pending = false;
+    e->hazards.join();
     for (int k = 0; k < kRing; k++) e->ring_out_rec[k] = e->ring_in_rec[k] = false;
     if (e->batch_open) {
         e->acc.ms_e2e = now_ms() - e->t0;
@@ -1185,6 +1194,7 @@ const char *kv_strerror(int code)
     case KV_ENOMEM: return "allocation failed";
     case KV_EHIP: return "HIP runtime failure";
     case KV_EUNSUP: return "path cannot serve this shape or request";
+    case KV_EBUSY: return "block or slot still in use by an un-waited call on the other stream";
     case KV_ENOSPC: return "not enough free HBM blocks or host slots";
     default: return "unknown code";
     }

@@ -28,6 +28,41 @@ struct Marks {
     }
 };
 
+// What un-waited calls still use, for refusing a call that would race with one
+// of them.  Work on one stream runs in order; the two streams run side by side
+// until something joins them (kv_wait, or a launch that carries both
+// directions).  A stamp equal to `epoch` means: used since the last join.
+struct Hazards {
+    std::vector<uint32_t> blk_read, blk_written, slot_read, slot_written;  // by stream_out / stream_in work
+    uint32_t epoch = 1;
+    void reset(size_t nb, size_t ns)
+    {
+        blk_read.assign(nb, 0); blk_written.assign(nb, 0);
+        slot_read.assign(ns, 0); slot_written.assign(ns, 0);
+        epoch = 1;
+    }
+    void join()
+    {
+        if (++epoch == 0xFFFFFFFFu) reset(blk_read.size(), slot_read.size());
+    }
+    // out part: reads blocks, writes slots, on stream_out; in part: reads slots,
+    // writes blocks, on stream_in.  Ids are in range (admission came first).
+    bool races(const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii, const int32_t *is,
+               int32_t ni) const
+    {
+        for (int32_t k = 0; k < no; k++)
+            if (blk_written[(size_t)oi[k]] == epoch || slot_read[(size_t)os[k]] == epoch) return true;
+        for (int32_t k = 0; k < ni; k++)
+            if (blk_read[(size_t)ii[k]] == epoch || slot_written[(size_t)is[k]] == epoch) return true;
+        return false;
+    }
+    void stamp(const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii, const int32_t *is, int32_t ni)
+    {
+        for (int32_t k = 0; k < no; k++) { blk_read[(size_t)oi[k]] = epoch; slot_written[(size_t)os[k]] = epoch; }
+        for (int32_t k = 0; k < ni; k++) { blk_written[(size_t)ii[k]] = epoch; slot_read[(size_t)is[k]] = epoch; }
+    }
+};
+
 constexpr int kRing = 8;  // descriptor sets that may be in flight
 // Tile counters of the link-bound kernels: one pair per stream (launches on a
 // stream run one after the other), each pair in a 256-byte stretch of its own.
@@ -62,6 +97,7 @@ struct kv_engine {
     int ring_cur = 0;
 
     dkv::Marks marks;
+    dkv::Hazards hazards;
     std::vector<std::pair<int32_t, int32_t>> sort_tmp;  // (slot, id)
 
     // stats

@@ -267,3 +267,43 @@ def test_in_heavy_interleave_for_every_launch_shape(lanes, wgs, u):
         case.rotate(rot)
         case.check()
         case.close()
+
+
+def test_racing_calls_are_refused_and_joined_calls_are_not():
+    """Un-waited calls run in order per stream and side by side across the two
+    streams: a call that would read what un-waited work on the other stream
+    writes (or the reverse) gets KV_EBUSY and changes nothing; a launch that
+    carries both directions joins the streams, so such rotations may follow one
+    another over the same blocks."""
+    sh = W.SHAPES["small8b"]
+    rot = W.simple_rotation(sh, 12, 10, seed=77)
+    inv = rot.inverse()
+    # two kernels on two streams: the inverse would read blocks the first call is still writing
+    case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, B.KV_PATH_ZEROCOPY, rot=rot)
+    case.rotate(rot)
+    assert case.eng.kv_rotate(inv.out_ids, inv.out_slots, inv.in_ids, inv.in_slots) == B.KV_EBUSY
+    assert case.eng.kv_swap_out(rot.in_ids[:2], rot.in_slots[:2]) == B.KV_EBUSY      # reads a block being written
+    assert case.eng.kv_swap_in(rot.out_slots[:2], rot.in_ids[:2]) == B.KV_EBUSY      # reads a slot being written
+    free = np.setdiff1d(np.arange(sh.n_hbm_blocks, dtype=np.int32), np.concatenate([rot.out_ids, rot.in_ids]))
+    assert case.eng.kv_swap_in(rot.in_slots[:2], rot.out_ids[:2]) == B.KV_EBUSY      # writes a block being read
+    case.check()                                                                     # only the first call happened
+    case.rotate(inv)                                                                 # after the wait it is fine
+    case.check()
+    # same stream, same direction: ordered, so reusing a slot is not a race
+    case.swap_out(rot.out_ids[:3], rot.out_slots[:3])
+    case.swap_out(rot.out_ids[3:6], rot.out_slots[:3])
+    case.swap_out(rot.out_ids[:3], rot.in_slots[:3])
+    # the other stream may run beside it on blocks and slots of its own
+    case.swap_in(rot.in_slots[3:6], free[:3])
+    case.check()
+    case.close()
+    # one launch for both directions: ordered against everything before and after
+    case, _ = make_case(sh, B.KV_HOST_LAYER_FIRST, B.KV_PATH_AUTO, rot=rot)
+    case.swap_in(rot.in_slots[:4], free[:4])          # stream_in only ...
+    case.rotate(W.Rotation(free[:4], rot.out_slots[:4], rot.in_ids[:4], rot.in_slots[4:8]))   # ... then a join over the same blocks
+    case.rotate(rot)
+    case.rotate(inv)
+    case.rotate(rot)
+    case.swap_out(rot.in_ids[:3], rot.out_slots[:3])   # after a join: ordered, although one stream only
+    case.check()
+    case.close()
