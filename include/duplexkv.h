@@ -64,7 +64,8 @@ extern "C" {
 #define KV_PATH_SDMA_STAGED 1  /* pack kernel -> staging in HBM -> hipMemcpyAsync (DMA engines), and the mirror */
 #define KV_PATH_ZEROCOPY    2  /* one kernel per direction, each on its own stream, reading / writing host memory directly */
 #define KV_PATH_NAIVE       3  /* one hipMemcpyAsync per segment: the baseline of Section 4.3.1, for the benchmark ladder */
-#define KV_PATH_FUSED       4  /* one kernel moves both directions, interleaved 1:1 per thread */
+#define KV_PATH_FUSED       4  /* one kernel moves both directions, interleaved per lane: 1:1, or, when the in list is the
+                                  longer one, with the out tiles spread evenly over the in tiles */
 #define KV_PATH_DMA_BLOCKS  5  /* one hipMemcpyAsync per block (runs of consecutive ids and slots merge): the
                                   "merged segments" design of Section 4.3.2; needs KV_HBM_BLOCK_FIRST and KV_HOST_BLOCK_FIRST */
 
