@@ -9,6 +9,7 @@
   python -m paper_2601_20309_amd.experiments linksweep     # bandwidth against segment size, copies and kernels
   python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
   python -m paper_2601_20309_amd.experiments sizes         # rotation rate against rotation size
+  python -m paper_2601_20309_amd.experiments ratio         # rates against the mix of the two directions
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
@@ -252,6 +253,33 @@ def sizes():
             assert calls[i & 1]() == 0 and eng.kv_wait() == 0
         ms, _, _ = _time_calls(eng, fn, 20 if n <= 128 else 6, warm=4)
         print(f"| {n} | {n * blk >> 20} | {ms * 1e3:.1f} | {2 * n * blk / ms / 1e6:.2f} |", flush=True)
+    eng.kv_destroy()
+
+
+def ratio():
+    """The link's rate region as the engine sees it: one rotation with n_out : n_in
+    scattered 2 MiB blocks (Llama-3-8B shape) at ratios from out-only to in-only."""
+    shape = W.SHAPES["llama3_8b"]
+    cache = _cache(shape)
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    print("\n| out : in blocks | step ms | out GB/s | in GB/s | sum GB/s |")
+    print("|---|---|---|---|---|")
+    for n_out, n_in in [(1024, 0), (1024, 256), (1024, 512), (1024, 768), (1024, 896), (1024, 1024), (960, 1024),
+                        (896, 1024), (832, 1024), (768, 1024), (512, 1024), (256, 1024), (0, 1024)]:
+        rot = W.simple_rotation(shape, n_out, n_in, seed=n_out * 7 + n_in)
+        calls = _rot_calls(eng, rot)
+        # only the forward steps are timed; the inverse steps restore the state
+        ts = []
+        for i in range(12):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+            if i >= 2 and not (i & 1):
+                ts.append((time.perf_counter() - t0) * 1e3)
+        ms = statistics.median(ts)
+        print(f"| {n_out} : {n_in} | {ms:.2f} | {n_out * blk / ms / 1e6:.2f} | {n_in * blk / ms / 1e6:.2f} | "
+              f"{(n_out + n_in) * blk / ms / 1e6:.2f} |", flush=True)
     eng.kv_destroy()
 
 
@@ -639,4 +667,4 @@ if __name__ == "__main__":
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
      "linksweep": linksweep, "serve": serve,
-     "sizes": sizes}[what]()
+     "sizes": sizes, "ratio": ratio}[what]()
