@@ -288,35 +288,54 @@ int mark_end(kv_engine *e, bool out_side, int k, hipStream_t s)
     return KV_OK;
 }
 
-// Vectors per lane per tile for the link-bound launches.
-int link_u(const kv_engine *e)
-{
-    return e->cfg.vecs_per_lane ? e->cfg.vecs_per_lane : 1;
-}
+// Launch shape of a link-bound kernel: workgroups, lanes per workgroup, vectors
+// per lane per tile.  Waves are the workers, each with one tile (U KiB per
+// direction at 16-byte vectors) in flight; workgroups only pack them.  What
+// saturates PCIe Gen5 x16 is bytes in flight; what a kernel running beside the
+// copy loses grows with the number of copy waves, steeply once the copy issues
+// more than the link drains.  So each kind of launch gets the smallest shape
+// that holds its rate both alone and beside an HBM-bound reader (measured,
+// scattered 2 MiB blocks, 4 GiB per direction; GB/s alone / beside the reader,
+// and what the reader keeps of its 6.5 TB/s):
+//  both directions in one launch, U = 1:
+//     80 waves  97.5 /  83.5 (5.59)     112 waves 100.7 /  99.9 (5.30)
+//     96 waves 100.2 /  96.4 (5.45)     144 waves 100.8 / 100.6 (4.94)
+//    (32 waves x U 4: 100.1 / 99.2 (5.52), but 99.4 instead of 100.1 at 256 MiB)
+//  swap-out alone: host-bound stores are paced by nothing but the link, and
+//  every wave beyond those that fill it only gets in the reader's way:
+//     U 1:  48 waves 56.7 / 46.6 (5.99)   64 waves 56.5 / 56.7 (5.34)   112 waves 55.8 / 56.8 (3.00)
+//     U 4:  16 waves 56.8 / 56.7 (5.68)   20 waves 56.7 / 56.8 (4.69)    24 waves 56.4 / 56.8 (3.75)
+//     U 8:  10 waves 56.7 / 51.0 (6.34)   12 waves 56.7 / 56.7 (5.93)
+//  swap-in alone:
+//     U 1:  64 waves 49.3 / 48.3 (5.49)   80 waves 57.4 / 56.8 (5.30)   112 waves 57.5 / 57.4 (4.88)
+//     U 4:  20 waves 55.2 / 54.2 (5.53)   24 waves 57.5 / 57.2 (5.44)
+//     U 8:  14 waves 57.5 / 51.3 (5.45)   16 waves 57.5 / 55.6 (5.36)
+// The same waves packed four or sixteen to a workgroup do no better.
+// A configured vecs_per_lane is kept (the wave count follows it); max_copy_wgs
+// counts workgroups of wg_lanes lanes and set alone keeps 256-lane workgroups;
+// wg_lanes set alone keeps the number of waves.
+enum LinkKind { kBoth, kOutOnly, kInOnly };
+struct LinkShape { int wgs, lanes, u; };
 
-// Launch shape of a link-bound kernel.  Waves are the workers, each with one
-// tile (1 KiB per direction at 16-byte vectors) in flight; workgroups only pack
-// them.  What saturates PCIe Gen5 x16 is bytes in flight, and what a kernel
-// running beside the copy loses grows with those same bytes, so the default is
-// the low end of the plateau.  Measured, scattered 2 MiB blocks, both directions
-// in one launch (GB/s at 256 + 256 MiB alone / at 4 + 4 GiB beside an HBM-bound
-// reader, and what the reader keeps of its 6.5 TB/s):
-//    64 waves  84.4 /  68.2 (5.75)     112 waves 100.1 / 100.0 (5.30)
-//    80 waves  96.5 /  83.5 (5.61)     124 waves 100.2 / 100.5 (5.14)
-//    96 waves  99.5 /  96.5 (5.47)     144 waves 100.1 / 100.6 (4.95)
-//   104 waves  99.9 /  99.4 (5.39)     192 waves 100.1 / 100.7 (4.50)
-// The same waves packed four to a workgroup (31 x 256 lanes) do slightly worse
-// beside the reader (97.8), so the default is one wave per workgroup, spread
-// over as many CUs.  One direction alone reaches the link's one-way rate with
-// the same shape (55.9 GB/s out, 57.3 in).
-// max_copy_wgs counts workgroups of wg_lanes lanes; set alone it keeps 256-lane
-// workgroups, wg_lanes set alone keeps the number of waves.
-void link_shape(const kv_engine *e, int &wgs, int &lanes)
+LinkShape link_shape(const kv_engine *e, LinkKind kind)
 {
-    constexpr int kWaves = 112;
-    const int cw = e->cfg.max_copy_wgs, cl = e->cfg.wg_lanes;
-    lanes = cl ? cl : (cw ? dkv::kThreads : dkv::kWave);
-    wgs = cw ? cw : std::max(1, kWaves * dkv::kWave / lanes);
+    const int cw = e->cfg.max_copy_wgs, cl = e->cfg.wg_lanes, cu = e->cfg.vecs_per_lane;
+    int u = cu ? cu : (kind == kOutOnly ? 8 : kind == kInOnly ? 4 : 1);
+    if (!cu) {  // whole tiles only: the segment must be a multiple of the tile
+        const uint64_t vec_per_seg = e->seg / (uint64_t)e->vec;
+        while (u > 1 && vec_per_seg % ((uint64_t)dkv::kWave * (uint64_t)u) != 0) u >>= 1;
+    }
+    int waves;
+    switch (kind) {
+    case kOutOnly: waves = u >= 8 ? 12 : u == 4 ? 16 : u == 2 ? 32 : 64; break;
+    case kInOnly: waves = u >= 8 ? 16 : u == 4 ? 24 : u == 2 ? 44 : 80; break;
+    default: waves = u >= 8 ? 20 : u == 4 ? 32 : u == 2 ? 64 : 112; break;
+    }
+    LinkShape s;
+    s.u = u;
+    s.lanes = cl ? cl : (cw ? dkv::kThreads : dkv::kWave);
+    s.wgs = cw ? cw : std::max(1, waves * dkv::kWave / s.lanes);
+    return s;
 }
 
 // HBM-bound pack / unpack launches want the whole chip.
@@ -331,11 +350,8 @@ int pack_wgs(const kv_engine *e)
 int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
 {
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
-    const int u = link_u(e);
     const bool fused = path == KV_PATH_FUSED && no > 0 && ni > 0;
-    int wgs1 = 0, lanes1 = 0;
-    link_shape(e, wgs1, lanes1);
-    auto params = [&](unsigned int *claim) {
+    auto params = [&](int u, unsigned int *claim) {
         MoveParams q = base_params(e, u);
         q.claim = claim;
         q.far_out = e->pool;
@@ -374,8 +390,8 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     if (fused) {
         // one launch on stream_out carries both directions; stream_in is joined
         // before (if it holds work) and after
-        const int wgs2 = wgs1, lanes2 = lanes1;
-        MoveParams p = params(e->claim);
+        const LinkShape sh = link_shape(e, kBoth);
+        MoveParams p = params(sh.u, e->claim);
         if (!desc(p, no, p.out) || !desc(p, ni, p.in)) return KV_EUNSUP;
         // in list longer: spread the out tiles over it instead of pairing 1:1
         if (p.full_tiles && p.in.tiles > p.out.tiles)
@@ -396,7 +412,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
                 e->b_i0 = e->ev_i0;
             }
         }
-        launch_move(u, e->vec, wgs2, lanes2, e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni}, true);
+        launch_move(sh.u, e->vec, sh.wgs, sh.lanes, e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni}, true);
         HIPTRY(e, hipGetLastError());
         e->acc.n_launches += 1;
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
@@ -404,19 +420,22 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ring_out[k], 0));
         return KV_OK;
     }
-    MoveParams p = params(e->claim);
-    DirDesc dout, din;
-    if (!desc(p, no, dout) || !desc(p, ni, din)) return KV_EUNSUP;
-    const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
     // One kernel per direction, each on its own stream.  When both run at once
     // they only reach the rate of the fused launch if each has at least one
-    // workgroup per CU (measured, one-wave workgroups per kernel, 256 + 256 MiB:
-    // 112 -> 70, 192 -> 77, 240 -> 87, 256 -> 99.9, 288 -> 99.5, 384 -> 98.5 GB/s;
-    // the same 256 waves packed as 64 x 256 lanes -> 76).
-    if (no > 0 && ni > 0 && !e->cfg.max_copy_wgs && !e->cfg.wg_lanes) {
-        wgs1 = 9 * (e->n_cus > 0 ? e->n_cus : 256) / 8;
-        lanes1 = dkv::kWave;
+    // workgroup per CU (measured, one-wave workgroups per kernel, U = 1, 256 + 256
+    // MiB: 112 -> 70, 192 -> 77, 240 -> 87, 256 -> 99.9, 288 -> 99.5, 384 -> 98.5
+    // GB/s; the same 256 waves packed as 64 x 256 lanes -> 76).
+    LinkShape sh_out = link_shape(e, kOutOnly), sh_in = link_shape(e, kInOnly);
+    if (no > 0 && ni > 0 && !e->cfg.max_copy_wgs && !e->cfg.wg_lanes && !e->cfg.vecs_per_lane) {
+        sh_out.wgs = sh_in.wgs = 9 * (e->n_cus > 0 ? e->n_cus : 256) / 8;
+        sh_out.lanes = sh_in.lanes = dkv::kWave;
+        sh_out.u = sh_in.u = 1;
     }
+    const MoveIds ids_out{d_o, d_o + no, nullptr, nullptr}, ids_in{nullptr, nullptr, d_i, d_i + ni};
+    // launches on stream_out draw from the first pair of counters, those on stream_in from the second
+    MoveParams p_out = params(sh_out.u, e->claim), p_in = params(sh_in.u, e->claim + kClaimStride);
+    p_out.in = p_in.out = none;
+    if (!desc(p_out, no, p_out.out) || !desc(p_in, ni, p_in.in)) return KV_EUNSUP;  // before anything is enqueued
     if (no > 0) {
         if (e->in_after_out && ni == 0 && e->in_dirty) {
             // a block this copy-out reads may still be being written by an earlier swap-in
@@ -426,10 +445,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         }
         if (upload_ids(true, false, e->s_out) != KV_OK) return KV_EHIP;
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
-        p.out = dout;
-        p.in = none;
-        p.claim = e->claim;  // launches on stream_out draw from the first pair of counters
-        launch_move(u, e->vec, wgs1, lanes1, e->s_out, p, ids_out, true);
+        launch_move(sh_out.u, e->vec, sh_out.wgs, sh_out.lanes, e->s_out, p_out, ids_out, true);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
@@ -442,10 +458,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         }
         if (upload_ids(false, true, e->s_in) != KV_OK) return KV_EHIP;
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
-        p.out = none;
-        p.in = din;
-        p.claim = e->claim + kClaimStride;  // launches on stream_in from the second
-        launch_move(u, e->vec, wgs1, lanes1, e->s_in, p, ids_in, true);
+        launch_move(sh_in.u, e->vec, sh_in.wgs, sh_in.lanes, e->s_in, p_in, ids_in, true);
         HIPTRY(e, hipGetLastError());
         if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
         e->acc.n_launches += 1;
