@@ -428,6 +428,48 @@ def interference():
         print(f"| {B.PATH_NAMES[path]} | {launch} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
               f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
         eng.kv_destroy()
+    # one direction at a time (what the eager step and a plain resumption issue), default shapes
+    print("\n| one direction, default shape | alone GB/s | beside reader GB/s | reader alone TB/s | reader beside TB/s |")
+    print("|---|---|---|---|---|")
+    rot = W.config_rotation(name, contiguous_slots=False)
+    inv = rot.inverse()
+    named = np.zeros(shape.n_hbm_blocks, bool)
+    named[rot.out_ids] = True; named[rot.in_ids] = True
+    others = np.flatnonzero(~named)[:19200].astype(np.int32)
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    read_bytes = len(others) * blk
+    assert eng.kv_reader_start(others, 6) == 0
+    rc, _, pm = eng.kv_reader_wait()
+    ms_pass = statistics.median(pm[1:])
+    for d, label in (("out", "swap-out (12 waves x 8 vectors)"), ("in", "swap-in (24 waves x 4 vectors)")):
+        def one(i):
+            a = rot if i % 2 == 0 else inv
+            rc = eng.kv_swap_out(a.out_ids, a.out_slots) if d == "out" else eng.kv_swap_in(a.in_slots, a.in_ids)
+            assert rc == 0 and eng.kv_wait() == 0
+        n_moved = (len(rot.out_ids) if d == "out" else len(rot.in_ids)) * blk
+        ms_alone, _, _ = _time_calls(eng, one, 4)
+        both, read_both = [], []
+        for i in range(4):
+            torch.cuda.synchronize()
+            assert eng.kv_reader_start(others, min(256, int(ms_alone / ms_pass * 1.5) + 4)) == 0
+            t0 = time.perf_counter()
+            one(i)
+            dt = (time.perf_counter() - t0) * 1e3
+            rc, _, pm2 = eng.kv_reader_wait()
+            assert rc == 0
+            if i >= 1:
+                both.append(dt)
+                acc, inside = 0.0, []
+                for p in pm2:
+                    if acc + p <= dt:
+                        inside.append(p)
+                    acc += p
+                inside = inside[1:] or pm2
+                read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
+        print(f"| {label} | {n_moved / ms_alone / 1e6:.2f} | {n_moved / statistics.median(both) / 1e6:.2f} | "
+              f"{read_bytes / ms_pass / 1e9:.2f} | {statistics.median(read_both):.2f} |", flush=True)
+    eng.kv_destroy()
 
 
 def reader():
