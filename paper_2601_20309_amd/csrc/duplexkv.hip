@@ -310,17 +310,24 @@ int mark_end(kv_engine *e, bool out_side, int k, hipStream_t s)
 //     U 1:  64 waves 49.3 / 48.3 (5.49)   80 waves 57.4 / 56.8 (5.30)   112 waves 57.5 / 57.4 (4.88)
 //     U 4:  20 waves 55.2 / 54.2 (5.53)   24 waves 57.5 / 57.2 (5.44)
 //     U 8:  14 waves 57.5 / 51.3 (5.45)   16 waves 57.5 / 55.6 (5.36)
+//  both directions in one launch with at least twice as much coming in as
+//  going out (the usual rotation once eager copies have run): the rate is the
+//  swap-in's, and 32 waves x U 4 hold it (out : in blocks, GB/s summed alone /
+//  beside the reader, reader):
+//     8 : 2048   112 x 1  57.4 / 57.3 (4.87)    32 x 4  57.5 / 57.3 (5.36)
+//  1024 : 2048   112 x 1  85.8 / 85.2 (5.09)    32 x 4  85.9 / 85.2 (5.38)
+//  1536 : 2048   112 x 1 100.1 / 98.8 (5.20)    32 x 4  99.6 / 97.9 (5.40)   (not taken: 112 x 1 stays)
 // The same waves packed four or sixteen to a workgroup do no better.
 // A configured vecs_per_lane is kept (the wave count follows it); max_copy_wgs
 // counts workgroups of wg_lanes lanes and set alone keeps 256-lane workgroups;
 // wg_lanes set alone keeps the number of waves.
-enum LinkKind { kBoth, kOutOnly, kInOnly };
+enum LinkKind { kBoth, kInHeavy, kOutOnly, kInOnly };
 struct LinkShape { int wgs, lanes, u; };
 
 LinkShape link_shape(const kv_engine *e, LinkKind kind)
 {
     const int cw = e->cfg.max_copy_wgs, cl = e->cfg.wg_lanes, cu = e->cfg.vecs_per_lane;
-    int u = cu ? cu : (kind == kOutOnly ? 8 : kind == kInOnly ? 4 : 1);
+    int u = cu ? cu : (kind == kOutOnly ? 8 : kind == kInOnly || kind == kInHeavy ? 4 : 1);
     if (!cu) {  // whole tiles only: the segment must be a multiple of the tile
         const uint64_t vec_per_seg = e->seg / (uint64_t)e->vec;
         while (u > 1 && vec_per_seg % ((uint64_t)dkv::kWave * (uint64_t)u) != 0) u >>= 1;
@@ -329,7 +336,7 @@ LinkShape link_shape(const kv_engine *e, LinkKind kind)
     switch (kind) {
     case kOutOnly: waves = u >= 8 ? 12 : u == 4 ? 16 : u == 2 ? 32 : 64; break;
     case kInOnly: waves = u >= 8 ? 16 : u == 4 ? 24 : u == 2 ? 44 : 80; break;
-    default: waves = u >= 8 ? 20 : u == 4 ? 32 : u == 2 ? 64 : 112; break;
+    default: waves = u >= 8 ? 20 : u == 4 ? 32 : u == 2 ? 64 : 112; break;  // kBoth and kInHeavy differ in u
     }
     LinkShape s;
     s.u = u;
@@ -390,7 +397,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     if (fused) {
         // one launch on stream_out carries both directions; stream_in is joined
         // before (if it holds work) and after
-        const LinkShape sh = link_shape(e, kBoth);
+        const LinkShape sh = link_shape(e, ni >= 2 * (int64_t)no ? kInHeavy : kBoth);
         MoveParams p = params(sh.u, e->claim);
         if (!desc(p, no, p.out) || !desc(p, ni, p.in)) return KV_EUNSUP;
         // in list longer: spread the out tiles over it instead of pairing 1:1
