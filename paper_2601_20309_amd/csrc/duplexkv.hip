@@ -278,6 +278,7 @@ int mark_end(kv_engine *e, bool out_side, int k, hipStream_t s)
         e->ring_out_rec[k] = true;
         e->b_o1 = e->ring_out[k];
         e->out_pending = true;
+        e->out_dirty = true;
     } else {
         HIPTRY(e, hipEventRecord(e->ring_in[k], s));
         e->ring_in_rec[k] = true;
@@ -440,6 +441,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
         e->b_i1 = e->ring_out[k];
         HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ring_out[k], 0));
+        e->out_dirty = false;
         return KV_OK;
     }
     // One kernel per direction, each on its own stream.  When both run at once
@@ -458,13 +460,26 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
     MoveParams p_out = params(sh_out.u, e->claim), p_in = params(sh_in.u, e->claim + kClaimStride);
     p_out.in = p_in.out = none;
     if (!desc(p_out, no, p_out.out) || !desc(p_in, ni, p_in.in)) return KV_EUNSUP;  // before anything is enqueued
+    // The block table promises that no block or slot is overwritten while an
+    // earlier transfer still reads it, and none read while an earlier one still
+    // writes it.  Its lists are conflict-free within a call but reuse, across
+    // calls, what earlier calls vacated; so each direction of a call first waits
+    // for what the other stream was given before this call, whether or not the
+    // call carries the other direction too (its own two directions still run
+    // side by side).
+    if (e->in_after_out && no > 0 && e->in_dirty) {
+        // a block this copy-out reads may still be being written by an earlier swap-in
+        HIPTRY(e, hipEventRecord(e->ev_join, e->s_in));
+        HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
+        e->in_dirty = false;
+    }
+    if (e->in_after_out && ni > 0 && e->out_dirty) {
+        // a block or slot this swap-in overwrites may still be read by an earlier copy-out
+        HIPTRY(e, hipEventRecord(e->ev_join_in, e->s_out));
+        HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join_in, 0));
+        e->out_dirty = false;
+    }
     if (no > 0) {
-        if (e->in_after_out && ni == 0 && e->in_dirty) {
-            // a block this copy-out reads may still be being written by an earlier swap-in
-            HIPTRY(e, hipEventRecord(e->ev_join, e->s_in));
-            HIPTRY(e, hipStreamWaitEvent(e->s_out, e->ev_join, 0));
-            e->in_dirty = false;
-        }
         if (upload_ids(true, false, e->s_out) != KV_OK) return KV_EHIP;
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
         launch_move(sh_out.u, e->vec, sh_out.wgs, sh_out.lanes, e->s_out, p_out, ids_out, true);
@@ -473,11 +488,6 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         e->acc.n_launches += 1;
     }
     if (ni > 0) {
-        if (e->in_after_out && no == 0) {
-            // a block or slot this swap-in overwrites may still be read by an earlier copy-out
-            HIPTRY(e, hipEventRecord(e->ev_join, e->s_out));
-            HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join, 0));
-        }
         if (upload_ids(false, true, e->s_in) != KV_OK) return KV_EHIP;
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
         launch_move(sh_in.u, e->vec, sh_in.wgs, sh_in.lanes, e->s_in, p_in, ids_in, true);
@@ -517,7 +527,7 @@ int run_naive(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, co
     if (no > 0) {
         HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
         e->b_o1 = e->ev_o1;
-        e->out_pending = true;
+        e->out_pending = e->out_dirty = true;
     }
     if (ni > 0) {
         HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
@@ -557,7 +567,7 @@ int run_dma_blocks(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t n
     if (no > 0) {
         HIPTRY(e, hipEventRecord(e->ev_o1, e->s_out));
         e->b_o1 = e->ev_o1;
-        e->out_pending = true;
+        e->out_pending = e->out_dirty = true;
     }
     if (ni > 0) {
         HIPTRY(e, hipEventRecord(e->ev_i1, e->s_in));
@@ -819,7 +829,7 @@ void free_engine(kv_engine *e)
     if (!e) return;
     auto ev = [](hipEvent_t &x) { if (x) { (void)hipEventDestroy(x); x = nullptr; } };
     for (int k = 0; k < kRing; k++) { ev(e->ring_out[k]); ev(e->ring_in[k]); }
-    ev(e->ev_o0); ev(e->ev_o1); ev(e->ev_i0); ev(e->ev_i1); ev(e->ev_join);
+    ev(e->ev_o0); ev(e->ev_o1); ev(e->ev_i0); ev(e->ev_i1); ev(e->ev_join); ev(e->ev_join_in);
     if (e->stage_out) (void)hipFree(e->stage_out);
     if (e->stage_in) (void)hipFree(e->stage_in);
     if (e->s_read) (void)hipStreamDestroy(e->s_read);
@@ -971,6 +981,7 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
     }
     for (hipEvent_t *x : {&e->ev_o0, &e->ev_o1, &e->ev_i0, &e->ev_i1}) ok = ok && hipEventCreate(x) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&e->ev_join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&e->ev_join_in, hipEventDisableTiming) == hipSuccess;
     if (!ok) return fail(KV_EHIP);
     e->marks.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
     e->hazards.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
@@ -1019,6 +1030,7 @@ int kv_wait(kv_engine *e)
         HIPTRY(e, hipStreamSynchronize(side == 0 ? e->s_out : e->s_in));
     }
     e->out_pending = e->in_pending = false;
+    e->out_dirty = e->in_dirty = false;
     e->hazards.join();
     for (int k = 0; k < kRing; k++) e->ring_out_rec[k] = e->ring_in_rec[k] = false;
     if (e->batch_open) {

@@ -101,11 +101,13 @@ struct kv_engine {
     std::vector<std::pair<int32_t, int32_t>> sort_tmp;  // (slot, id)
 
     // stats
-    hipEvent_t ev_o0 = nullptr, ev_o1 = nullptr, ev_i0 = nullptr, ev_i1 = nullptr, ev_join = nullptr;
+    hipEvent_t ev_o0 = nullptr, ev_o1 = nullptr, ev_i0 = nullptr, ev_i1 = nullptr;
+    hipEvent_t ev_join = nullptr, ev_join_in = nullptr;  // stream_out waits for stream_in / the reverse
     hipEvent_t b_o0 = nullptr, b_o1 = nullptr, b_i0 = nullptr, b_i1 = nullptr;  // this batch's first start / last end
     bool batch_open = false;
     bool out_pending = false, in_pending = false;  // work enqueued since the last kv_wait
     bool in_dirty = false;                         // stream_in holds work stream_out has not joined
+    bool out_dirty = false;                        // stream_out holds work stream_in has not joined
     bool in_after_out = false;                     // block table in use: in-only work waits for earlier out work
     double t0 = 0;
     kv_stats acc{}, last{};

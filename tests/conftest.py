@@ -25,3 +25,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def say(request, capfd):
+    """Progress lines of long GPU tests, printed past pytest's capture so that
+    a run of several minutes is seen to be alive."""
+    import time
+    t0 = time.time()
+
+    def emit(msg):
+        with capfd.disabled():
+            print(f"  [{request.node.name} +{time.time() - t0:5.1f}s] {msg}", flush=True)
+    return emit

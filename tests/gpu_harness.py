@@ -85,61 +85,85 @@ class BigCase:
     """Full-size check that needs little host memory.
 
     The cache is drawn on the GPU.  The oracle works on host images that are
-    allocated lazily: only the blocks and slots a rotation names are ever filled
-    (with the exact bytes the GPU holds) or touched, which is all the oracle
-    reads or writes.  Named blocks and slots are compared with the oracle's
-    result byte for byte; every other block is compared with a regenerated
-    image on the GPU, every other slot with the fill pattern it was given.
+    allocated lazily: only the blocks and slots a rotation (or a reader) names
+    are ever filled (with the exact bytes the GPU holds) or touched, which is
+    all the oracle reads or writes.  Named blocks and slots are compared with
+    the oracle's result byte for byte; every other block is compared with a
+    regenerated image on the GPU, every other slot with the fill pattern it was
+    given.  Device <-> host traffic of the check itself goes in pieces of about
+    1 GiB; `say` (a callable taking one string) reports progress.
     """
 
     FILL = 0xA5
+    PIECE = 1 << 30
 
-    def __init__(self, name, layout=B.KV_HOST_BLOCK_FIRST, path=B.KV_PATH_AUTO, shape=None, **cfgkw):
+    def __init__(self, name, layout=B.KV_HOST_BLOCK_FIRST, path=B.KV_PATH_AUTO, shape=None, say=None, **cfgkw):
         self.name, self.layout = name, layout
+        self.say = say or (lambda msg: None)
         self.shape = shape or W.SHAPES[name]
         self.seed = W.value_seed(name)
         self.cfg = B.make_config(self.shape, layout, path, **cfgkw)
         self.oshape = O.shape_of(self.shape, layout)
+        self.per_piece = max(1, self.PIECE // O.block_bytes(self.oshape))
         self.cache = W.cache_image(self.shape, self.seed, device="cuda")
         torch.cuda.synchronize()
+        self.say(f"{name}: cache of {O.cache_bytes(self.oshape) >> 30} GiB drawn")
         self.eng = B.Engine(self.cfg, self.cache.data_ptr())
         self.pool_u8 = self.eng.host_pool_array()
         self.pool_u8[:] = self.FILL
+        self.say(f"{name}: pool of {O.pool_bytes(self.oshape) >> 30} GiB filled")
         self.ref_cache = np.empty(O.cache_bytes(self.oshape), dtype=np.uint8)   # lazily backed
         self.ref_pool = np.empty(O.pool_bytes(self.oshape), dtype=np.uint8)
         self.touched_blocks, self.touched_slots = set(), set()
-        self.staged = {}
 
-    # views [L,2,N,P,H,D] (int16) of the host images and the pinned pool
+    # views [L,2,N,P,H,D] (uint16) of the host images and the pinned pool
     def _cv(self):
         return V.hbm_view(self.shape, self.ref_cache.view(np.uint16))
 
     def _pv(self, buf):
         return V.pool_view(self.shape, buf.view(np.uint16), self.layout)
 
+    def _pieces(self, items):
+        items = list(items)
+        for c0 in range(0, len(items), self.per_piece):
+            yield items[c0:c0 + self.per_piece]
+
+    def _device_blocks(self, ids):
+        """[L,2,len(ids),P,H,D] uint16 copy of the named blocks as the GPU holds them."""
+        idx = torch.tensor(ids, device="cuda")
+        return self.cache.view(torch.int16)[:, :, idx].cpu().numpy().view(np.uint16)
+
     def stage(self, slots, seed_offset=50):
         """Put seeded blocks into host slots (pinned pool and reference alike)."""
         slots = np.asarray(slots)
-        blocks = W.staged_blocks(self.shape, len(slots), self.seed + seed_offset, device="cuda")
-        arr = blocks.view(torch.int16).cpu().numpy().view(np.uint16).transpose(1, 2, 0, 3, 4, 5)
-        self._pv(self.pool_u8)[:, :, slots] = arr
-        self._pv(self.ref_pool)[:, :, slots] = arr
+        k = 0
+        for part in self._pieces(slots):
+            blocks = W.staged_blocks(self.shape, len(part), self.seed + seed_offset + k, device="cuda")
+            arr = blocks.view(torch.int16).cpu().numpy().view(np.uint16).transpose(1, 2, 0, 3, 4, 5)
+            self._pv(self.pool_u8)[:, :, part] = arr
+            self._pv(self.ref_pool)[:, :, part] = arr
+            k += 1
         self.touched_slots.update(int(s) for s in slots)
+        self.say(f"{self.name}: {len(slots)} slots staged")
 
-    def _sync_ref(self, ids, slots):
-        """Bring blocks / slots that are about to be named into the reference."""
+    def sync_ref(self, ids, slots=(), read_only=False):
+        """Bring blocks / slots that are about to be named into the reference.
+        Blocks that are only read (the reader's) are mirrored for the oracle but
+        stay among the blocks check() compares with the regenerated image."""
         new_b = [int(b) for b in ids if int(b) not in self.touched_blocks]
-        if new_b:
-            idx = torch.tensor(new_b, device="cuda")
-            self._cv()[:, :, new_b] = self.cache.view(torch.int16)[:, :, idx].cpu().numpy().view(np.uint16)
+        for part in self._pieces(new_b):
+            self._cv()[:, :, part] = self._device_blocks(part)
+        if not read_only:
             self.touched_blocks.update(new_b)
         new_s = [int(s) for s in slots if int(s) not in self.touched_slots]
-        if new_s:
-            self._pv(self.ref_pool)[:, :, new_s] = self._pv(self.pool_u8)[:, :, new_s]
-            self.touched_slots.update(new_s)
+        for part in self._pieces(new_s):
+            self._pv(self.ref_pool)[:, :, part] = self._pv(self.pool_u8)[:, :, part]
+        self.touched_slots.update(new_s)
+        if new_b or new_s:
+            self.say(f"{self.name}: {len(new_b)} blocks and {len(new_s)} slots mirrored on the host")
 
     def rotate(self, rot):
-        self._sync_ref(np.concatenate([rot.out_ids, rot.in_ids]), np.concatenate([rot.out_slots, rot.in_slots]))
+        self.sync_ref(np.concatenate([rot.out_ids, rot.in_ids]), np.concatenate([rot.out_slots, rot.in_slots]))
         assert self.eng.kv_rotate(rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots) == 0
         assert O.rotate(self.oshape, self.ref_cache, self.ref_pool, rot.out_ids, rot.out_slots,
                         rot.in_ids, rot.in_slots, threads=8) == 0
@@ -149,29 +173,29 @@ class BigCase:
         tb = sorted(self.touched_blocks)
         ts = sorted(self.touched_slots)
         # named blocks and slots: against the oracle
-        for c0 in range(0, len(tb), 256):
-            ids = tb[c0:c0 + 256]
-            got = self.cache.view(torch.int16)[:, :, torch.tensor(ids, device="cuda")].cpu().numpy().view(np.uint16)
-            assert np.array_equal(got, self._cv()[:, :, ids]), "named HBM blocks differ from the oracle"
-        for c0 in range(0, len(ts), 256):
-            sl = ts[c0:c0 + 256]
+        for ids in self._pieces(tb):
+            assert np.array_equal(self._device_blocks(ids), self._cv()[:, :, ids]), \
+                "named HBM blocks differ from the oracle"
+        self.say(f"{self.name}: {len(tb)} named blocks equal the oracle's")
+        for sl in self._pieces(ts):
             assert np.array_equal(self._pv(self.pool_u8)[:, :, sl], self._pv(self.ref_pool)[:, :, sl]), \
                 "named host slots differ from the oracle"
+        self.say(f"{self.name}: {len(ts)} named slots equal the oracle's")
         # every other block: against a regenerated image
         again = W.cache_image(self.shape, self.seed, device="cuda")
-        if tb:
-            idx = torch.tensor(tb, device="cuda")
+        for ids in self._pieces(tb):
+            idx = torch.tensor(ids, device="cuda")
             again[:, :, idx] = self.cache[:, :, idx]
         assert torch.equal(again.view(torch.int16), self.cache.view(torch.int16)), "an un-named block changed"
         del again
         # every other slot: still the fill pattern
         mask = np.ones(self.shape.n_host_slots, dtype=bool)
         mask[ts] = False
-        other = np.flatnonzero(mask)
         pv = self._pv(self.pool_u8)
         pat = np.uint16(self.FILL * 0x0101)
-        for c0 in range(0, len(other), 128):
-            assert (pv[:, :, other[c0:c0 + 128]] == pat).all(), "an un-named slot changed"
+        for sl in self._pieces(np.flatnonzero(mask)):
+            assert (pv[:, :, sl] == pat).all(), "an un-named slot changed"
+        self.say(f"{self.name}: every other block and slot unchanged")
 
     def close(self):
         self.eng.kv_destroy()

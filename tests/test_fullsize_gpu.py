@@ -1,10 +1,9 @@
 """Parity at BASELINE's full sizes, in the launch configuration bench.py times
 (default config: AUTO path, block-first pool, library-owned pool and streams)."""
-import dataclasses
-
 import numpy as np
 import pytest
 
+from oracle import kv_oracle as O
 from paper_2601_20309_amd import binding as B
 from paper_2601_20309_amd import workloads as W
 from tests.gpu_harness import BigCase
@@ -64,18 +63,64 @@ def test_batch_rotation_full_size():
     (B.KV_PATH_AUTO, B.KV_HOST_BLOCK_FIRST, 0),
     (B.KV_PATH_SDMA_STAGED, B.KV_HOST_LAYER_FIRST, 1),
 ])
-def test_long70b_shape_quarter_size(path, layout, chunk_layers):
-    """configs[3] shape (80 layers, 64 KiB segments, 10 MiB blocks) at a quarter of
-    its block counts: 2 x 8192-token requests each way, chunked per layer on the
-    DMA path.  The full-size run is bench.py --workload long70b."""
-    shape = dataclasses.replace(W.SHAPES["long70b"], n_hbm_blocks=1152, n_host_slots=1024)
-    rot = W.request_rotation(shape, [8192] * 2, [8192] * 2, seed=W.BASE_SEED + 103, contiguous_slots=True)
-    assert len(rot.out_ids) == 512
-    case = BigCase("long70b", layout=layout, path=path, shape=shape, chunk_layers=chunk_layers)
+def test_long70b_rotation_full_size(path, layout, chunk_layers, say):
+    """configs[3]: 80 layers, 64 KiB segments, 10 MiB blocks, a 45 GiB cache and a
+    40 GiB pool; two 32768-token requests leave while two come back (20 GiB each
+    way, the transfer size of the paper's Section 5.4 / Table 2 per direction), in
+    one launch on the default path and chunked per layer on the DMA path."""
+    shape = W.SHAPES["long70b"]
+    assert shape.n_hbm_blocks == 4608 and shape.n_host_slots == 4096
+    rot = W.config_rotation("long70b", contiguous_slots=chunk_layers == 1)
+    assert len(rot.out_ids) == len(rot.in_ids) == 2048
+    case = BigCase("long70b", layout=layout, path=path, chunk_layers=chunk_layers, say=say)
+    blk = B.kv_block_bytes(case.cfg)
+    assert blk == 10 << 20 and B.kv_cache_bytes(case.cfg) == 45 << 30
     case.stage(rot.in_slots)
     case.rotate(rot)
     case.check()
+    st = case.eng.kv_last_stats()
+    assert st["bytes_out"] == st["bytes_in"] == 20 << 30
     if chunk_layers == 1:
-        # 80 layer chunks per direction, each one pack/unpack kernel + 2 plane copies
-        assert case.eng.kv_last_stats()["n_launches"] == 2 * 80 * 3
+        # 80 layer chunks per direction, each one pack / unpack kernel + 2 plane copies
+        assert st["path_used"] == B.KV_PATH_SDMA_STAGED and st["n_launches"] == 2 * 80 * 3
+    else:
+        assert st["path_used"] == B.KV_PATH_FUSED and st["n_launches"] == 1
+    case.close()
+
+
+def test_interference_rotation_beside_the_reader_full_size(say):
+    """configs[4]: Llama-3-8B shape, 48 GiB cache; eight 4096-token requests leave
+    while eight come back (2048 + 2048 blocks, 4 GiB each way) and the decode
+    reader streams 19200 other blocks (37.5 GiB per pass) at the same time.  Cache,
+    pool and the reader's checksum are all checked against the oracle."""
+    shape = W.SHAPES["interference"]
+    assert shape.n_hbm_blocks == 24576
+    rot = W.config_rotation("interference")
+    assert len(rot.out_ids) == len(rot.in_ids) == 2048
+    named = np.zeros(shape.n_hbm_blocks, dtype=bool)
+    named[rot.out_ids] = named[rot.in_ids] = True
+    others = np.flatnonzero(~named)
+    read_ids = np.random.default_rng(W.BASE_SEED + 204).permutation(others)[:19200].astype(np.int32)
+    case = BigCase("interference", say=say)
+    case.stage(rot.in_slots)
+    case.sync_ref(read_ids, read_only=True)
+    rc, want = O.read_checksum(case.oshape, case.ref_cache, read_ids)
+    assert rc == 0
+    say("oracle checksum of the reader's blocks done")
+    passes = 16                           # ~110 ms of reading; the rotation needs ~85 ms
+    case.sync_ref(np.concatenate([rot.out_ids, rot.in_ids]), np.concatenate([rot.out_slots, rot.in_slots]))
+    assert case.eng.kv_reader_start(read_ids, passes) == 0
+    case.rotate(rot)                      # enqueued while the reader runs
+    rc, got, ms = case.eng.kv_reader_wait()
+    assert rc == 0 and len(ms) == passes and got == (want * passes) % (1 << 64)
+    case.check()
+    st = case.eng.kv_last_stats()
+    assert st["path_used"] == B.KV_PATH_FUSED and st["bytes_out"] == st["bytes_in"] == 4 << 30
+    say(f"rotation {st['ms_out']:.1f} ms beside a reader of {sum(ms):.1f} ms in {passes} passes")
+    # and the inverse, with the reader over the same blocks once more
+    assert case.eng.kv_reader_start(read_ids, 1) == 0
+    case.rotate(rot.inverse())
+    rc, got, _ = case.eng.kv_reader_wait()
+    assert rc == 0 and got == want
+    case.check()
     case.close()

@@ -155,11 +155,12 @@ def test_race_rule_on_the_gpu():
     s.close()
 
 
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY])
 @pytest.mark.parametrize("seed", [0, 1])
 @pytest.mark.parametrize("layout", [B.KV_HOST_BLOCK_FIRST, B.KV_HOST_LAYER_FIRST])
-def test_random_schedules_match_the_oracle(layout, seed):
+def test_random_schedules_match_the_oracle(layout, seed, path):
     sh = W.KVShape(2, 2, 64, 4, n_hbm_blocks=24, n_host_slots=40)
-    s = BothSides(sh, layout, max_req=6, seed=seed)
+    s = BothSides(sh, layout, max_req=6, seed=seed, path=path)
     rng = np.random.default_rng(500 + seed)
     for step in range(120):
         op = rng.integers(0, 10)
@@ -227,12 +228,14 @@ def test_llama_shape_preemption_moves_one_block_per_request():
     eng.kv_destroy()
 
 
-def test_back_to_back_table_calls_without_waiting():
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY])
+def test_back_to_back_table_calls_without_waiting(path):
     """Eager copies, preemptions and resumptions enqueued back to back: blocks that
     one call vacates are refilled by the next while the first may still be running,
-    so this only passes if the table orders its transfers across the two streams."""
+    so this only passes if the table orders its transfers across the two streams
+    (on the two-kernel path every rotation puts one kernel on each stream)."""
     sh = W.KVShape(8, 8, 128, 16, n_hbm_blocks=96, n_host_slots=256)     # 512 KiB blocks
-    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=6, seed=7)
+    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=6, seed=7, path=path)
     for r in range(4):
         s.append(r, 16 * 22 + 5)              # 22 full blocks + a tail; 4 x 23 = 92 of 96 blocks
     s.check(6)
