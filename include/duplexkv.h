@@ -50,6 +50,7 @@ extern "C" {
 #define KV_EUNSUP   (-7)  /* the chosen path cannot serve this shape or request */
 #define KV_ENOSPC   (-8)  /* block table: not enough free HBM blocks or host slots */
 #define KV_EBUSY    (-9)  /* a block or slot is still used the other way round by an un-waited call on the other stream */
+#define KV_E2BIG    (-10) /* kv_rotate_static: more blocks than its scratch array holds */
 
 /* ---- host pool layouts ---- */
 #define KV_HOST_BLOCK_FIRST 0
@@ -167,6 +168,33 @@ int kv_swap_in(kv_engine *engine, const int32_t *host_slots, const int32_t *bloc
 int kv_rotate(kv_engine *engine,
               const int32_t *out_block_ids, const int32_t *out_host_slots, int32_t n_out,
               const int32_t *in_block_ids, const int32_t *in_host_slots, int32_t n_in);
+
+/*
+ * kv_rotate() for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops that must not reach hipMalloc, harnesses that forbid it.
+ * No engine: the caller passes the configuration (shape, layouts and, if
+ * wanted, the launch-shape fields; path must be KV_PATH_AUTO or KV_PATH_FUSED),
+ * the cache (device pointer, kv_cache_bytes), the pool (pinned, device-mapped
+ * host pointer, kv_pool_bytes) and the hipStream_t to enqueue on (NULL = the
+ * default stream), all on the current device.  The call allocates nothing, on
+ * the device or through any library: the move kernel's step counters and the
+ * device copy of the four id lists live in a fixed array of device memory that
+ * belongs to the library (64 KiB + 256 bytes per GPU, held until the process
+ * ends), which bounds a call to n_out + n_in <= KV_STATIC_MAX_BLOCKS (KV_E2BIG
+ * beyond that; nothing enqueued).  Admission and result are kv_rotate's: one
+ * launch carries both directions (or the one that is not empty).  Asynchronous:
+ * the id lists are read before the call returns; completion is the stream's
+ * (hipStreamSynchronize, or an event of the caller's).  Every call on a GPU
+ * shares that GPU's array, so calls on one GPU must be ordered one after the
+ * other (the same stream, or streams the caller orders): two calls that overlap
+ * in time race on the id lists.  One host thread at a time, process-wide.  No
+ * KV_EBUSY tracking: ordering against other work on the same blocks is the
+ * stream's order.
+ */
+#define KV_STATIC_MAX_BLOCKS 8192
+int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, void *stream,
+                     const int32_t *out_block_ids, const int32_t *out_host_slots, int32_t n_out,
+                     const int32_t *in_block_ids, const int32_t *in_host_slots, int32_t n_in);
 
 /* Blocks until everything enqueued so far is done; the host pool is then
  * coherent for CPU reads.  Closes the interval kv_last_stats() reports. */

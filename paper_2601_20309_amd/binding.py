@@ -16,8 +16,9 @@ import torch  # noqa: F401
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduplexkv.so")
 
-KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP, KV_ENOSPC, KV_EBUSY = \
-    0, -1, -2, -3, -4, -5, -6, -7, -8, -9
+KV_OK, KV_EINVAL, KV_ERANGE, KV_EDUP, KV_EOVERLAP, KV_ENOMEM, KV_EHIP, KV_EUNSUP, KV_ENOSPC, KV_EBUSY, KV_E2BIG = \
+    0, -1, -2, -3, -4, -5, -6, -7, -8, -9, -10
+KV_STATIC_MAX_BLOCKS = 8192
 KV_BLOCK_DIRTY, KV_BLOCK_FULL, KV_BLOCK_SYNCED, KV_BLOCK_HOST = 1, 2, 3, 4
 KV_HOST_BLOCK_FIRST, KV_HOST_LAYER_FIRST = 0, 1
 KV_HBM_LAYER_FIRST, KV_HBM_BLOCK_FIRST = 0, 1
@@ -26,7 +27,7 @@ KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSE
 PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused", 5: "dma_blocks"}
 
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
-           "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_wait",
+           "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_rotate_static", "kv_wait",
            "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
            "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate", "kv_table_rotate_eager",
            "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_sched_vlt", "kv_sched_lvf",
@@ -89,6 +90,8 @@ def _load() -> C.CDLL:
     L.kv_swap_in.argtypes = [C.c_void_p, p32, p32, C.c_int32]
     L.kv_rotate.restype = C.c_int
     L.kv_rotate.argtypes = [C.c_void_p, p32, p32, C.c_int32, p32, p32, C.c_int32]
+    L.kv_rotate_static.restype = C.c_int
+    L.kv_rotate_static.argtypes = [pcfg, C.c_void_p, C.c_void_p, C.c_void_p, p32, p32, C.c_int32, p32, p32, C.c_int32]
     L.kv_wait.restype = C.c_int
     L.kv_wait.argtypes = [C.c_void_p]
     L.kv_host_pool.restype = C.c_int
@@ -166,6 +169,15 @@ def kv_validate(cfg, out_block_ids, out_host_slots, in_block_ids, in_host_slots,
     assert no == no2 and ni == ni2
     return lib.kv_validate(C.byref(cfg), po, ps, no if n_out is None else n_out,
                            pi, pis, ni if n_in is None else n_in)
+
+
+def kv_rotate_static(cfg, hbm_cache_ptr: int, host_pool_ptr: int, stream: int,
+                     out_block_ids, out_host_slots, in_block_ids, in_host_slots) -> int:
+    po, no, k1 = _ids(out_block_ids); ps, no2, k2 = _ids(out_host_slots)
+    pi, ni, k3 = _ids(in_block_ids); pis, ni2, k4 = _ids(in_host_slots)
+    assert no == no2 and ni == ni2
+    return lib.kv_rotate_static(C.byref(cfg), C.c_void_p(hbm_cache_ptr or None), C.c_void_p(host_pool_ptr or None),
+                                C.c_void_p(stream or None), po, ps, no, pi, pis, ni)
 
 
 def kv_probe_link(nbytes: int, reps: int = 5) -> dict:

@@ -849,6 +849,104 @@ void free_engine(kv_engine *e)
     delete e;
 }
 
+// ---- the entry point that allocates nothing --------------------------------
+// Everything kv_rotate keeps in memory the engine allocated (the step counters
+// of the move kernel and the device copy of the call's four id lists) lives,
+// for kv_rotate_static, in one file-scope array of device memory.  Every GPU the
+// library runs on holds its own copy of the array, at its own address, until
+// the process ends.  Layout: [0, 256) the counter pair, then the id lists as
+// [out_ids | out_slots | in_ids | in_slots].
+constexpr size_t kStaticIdsOff = 256;
+constexpr size_t kStaticBytes = kStaticIdsOff + 2 * (size_t)KV_STATIC_MAX_BLOCKS * sizeof(int32_t);
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// In host code `scratch` is only a handle for the symbol, not a device address;
+// the address on the current device comes from hipGetSymbolAddress, once per
+// device, and only that pointer is ever handed to a kernel.
+constexpr int kStaticMaxDevices = 64;
+unsigned char *g_scratch_ptr[kStaticMaxDevices] = {};
+
+int static_scratch(unsigned char *&ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticMaxDevices) {
+        (void)hipGetLastError();
+        return KV_EHIP;
+    }
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || !p) {
+            (void)hipGetLastError();
+            fprintf(stderr, "duplexkv: hipGetSymbolAddress(scratch) failed on device %d: %s\n", dev,
+                    hipGetErrorString(err));
+            return KV_EHIP;
+        }
+        g_scratch_ptr[dev] = (unsigned char *)p;
+    }
+    ptr = g_scratch_ptr[dev];
+    return KV_OK;
+}
+
+// The id lists travel to the scratch array as kernel arguments (copied at
+// launch, so the caller's arrays are free again when the call returns, and no
+// pinned staging buffer is needed): kIdsPerLaunch ints per launch.  The first
+// launch of a call also puts the counter pair to zero.
+constexpr uint32_t kIdsPerLaunch = 960;
+struct IdChunk {
+    int32_t v[kIdsPerLaunch];
+};
+
+__global__ __launch_bounds__(256) void kv_ids_kernel(const IdChunk c, int32_t *dst, uint32_t n,
+                                                     unsigned int *zero)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) dst[i] = c.v[i];
+    if (zero && threadIdx.x < 2) zero[threadIdx.x] = 0u;
+}
+
+// Admission without marks of cache size: sorted copies in static host arrays.
+int32_t g_sorted[4][KV_STATIC_MAX_BLOCKS];
+
+bool sorted_has_repeat(const int32_t *p, int32_t n)
+{
+    for (int32_t i = 1; i < n; i++)
+        if (p[i] == p[i - 1]) return true;
+    return false;
+}
+
+bool sorted_share(const int32_t *a, int32_t na, const int32_t *b, int32_t nb)
+{
+    int32_t i = 0, j = 0;
+    while (i < na && j < nb) {
+        if (a[i] == b[j]) return true;
+        if (a[i] < b[j]) i++;
+        else j++;
+    }
+    return false;
+}
+
+int admit_static(const kv_config *c, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
+                 const int32_t *is, int32_t ni)
+{
+    if (list_bad(oi, no) || list_bad(os, no) || list_bad(ii, ni) || list_bad(is, ni)) return KV_EINVAL;
+    if ((int64_t)no + ni > KV_STATIC_MAX_BLOCKS) return KV_E2BIG;
+    if (out_of_range(oi, no, c->n_hbm_blocks) || out_of_range(ii, ni, c->n_hbm_blocks) ||
+        out_of_range(os, no, c->n_host_slots) || out_of_range(is, ni, c->n_host_slots))
+        return KV_ERANGE;
+    const int32_t *src[4] = {oi, os, ii, is};
+    const int32_t len[4] = {no, no, ni, ni};
+    bool dup = false;
+    for (int k = 0; k < 4; k++) {
+        if (len[k]) memcpy(g_sorted[k], src[k], (size_t)len[k] * sizeof(int32_t));
+        std::sort(g_sorted[k], g_sorted[k] + len[k]);
+        dup = dup || sorted_has_repeat(g_sorted[k], len[k]);
+    }
+    if (dup) return KV_EDUP;
+    if (sorted_share(g_sorted[0], no, g_sorted[2], ni) || sorted_share(g_sorted[1], no, g_sorted[3], ni))
+        return KV_EOVERLAP;
+    return KV_OK;
+}
+
 double median(std::vector<double> v)
 {
     std::sort(v.begin(), v.end());
@@ -1065,6 +1163,100 @@ int kv_last_stats(kv_engine *e, kv_stats *out)
     return KV_OK;
 }
 
+int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, void *stream,
+                     const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii, const int32_t *is,
+                     int32_t ni)
+{
+    if (!config_ok(cfg) || !hbm_cache || !host_pool) return KV_EINVAL;
+    if (cfg->path != KV_PATH_AUTO && cfg->path != KV_PATH_FUSED) return KV_EUNSUP;
+    int rc = admit_static(cfg, oi, os, no, ii, is, ni);
+    if (rc != KV_OK) return rc;
+    // an engine that exists only on this stack frame, so that the launch helpers
+    // of the other paths serve here too; nothing in it owns memory
+    kv_engine view;
+    kv_engine *e = &view;
+    e->cfg = *cfg;
+    e->seg = seg_of(cfg);
+    e->n_planes = 2u * (uint32_t)cfg->n_layers;
+    e->block_bytes = kv_block_bytes(cfg);
+    e->cache_bytes = kv_cache_bytes(cfg);
+    e->pool_bytes = kv_pool_bytes(cfg);
+    e->hbm = (uint8_t *)hbm_cache;
+    e->pool = (uint8_t *)host_pool;
+    e->vec = pick_vec(e);
+    // both pointers are checked before a kernel is given them
+    {
+        hipDeviceptr_t base = nullptr;
+        size_t span = 0;
+        if (hipMemGetAddressRange(&base, &span, (hipDeviceptr_t)hbm_cache) != hipSuccess ||
+            (uintptr_t)hbm_cache + e->cache_bytes > (uintptr_t)base + span) {
+            (void)hipGetLastError();
+            fprintf(stderr, "duplexkv: hbm_cache is not a device allocation of the configured size\n");
+            return KV_EINVAL;
+        }
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, host_pool) != hipSuccess || at.type != hipMemoryTypeHost) {
+            (void)hipGetLastError();
+            fprintf(stderr, "duplexkv: host_pool is not pinned host memory\n");
+            return KV_EINVAL;
+        }
+        if (hipMemGetAddressRange(&base, &span, (hipDeviceptr_t)host_pool) == hipSuccess) {
+            if ((uintptr_t)host_pool + e->pool_bytes > (uintptr_t)base + span) {
+                fprintf(stderr, "duplexkv: host_pool allocation is smaller than the configured pool\n");
+                return KV_EINVAL;
+            }
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    if (no == 0 && ni == 0) return KV_OK;
+    const LinkKind kind = no == 0 ? kInOnly : ni == 0 ? kOutOnly : ni >= 2 * (int64_t)no ? kInHeavy : kBoth;
+    const LinkShape sh = link_shape(e, kind);
+    MoveParams p = base_params(e, sh.u);
+    p.far_out = p.far_in = e->pool;
+    pool_strides(e, p.far_slot_stride_out, p.far_plane_stride_out);
+    p.far_slot_stride_in = p.far_slot_stride_out;
+    p.far_plane_stride_in = p.far_plane_stride_out;
+    p.plane_major = cfg->host_layout == KV_HOST_LAYER_FIRST ? 1u : 0u;
+    p.out = DirDesc{(uint32_t)no, 0, 0, 0};
+    p.in = DirDesc{(uint32_t)ni, 0, 0, 0};
+    if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles) ||
+        !dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles))
+        return KV_EUNSUP;
+    if (p.full_tiles && p.out.tiles > 0 && p.in.tiles > p.out.tiles)
+        p.mix_q = (((uint64_t)p.out.tiles << 32) + p.in.tiles - 1) / p.in.tiles;
+    unsigned char *sc = nullptr;
+    rc = static_scratch(sc);
+    if (rc != KV_OK) return rc;
+    p.claim = reinterpret_cast<unsigned int *>(sc);
+    int32_t *ids = reinterpret_cast<int32_t *>(sc + kStaticIdsOff);
+    hipStream_t s = (hipStream_t)stream;
+    // the four lists, back to back, through kernel arguments
+    const int32_t *src[4] = {oi, os, ii, is};
+    const uint32_t len[4] = {(uint32_t)no, (uint32_t)no, (uint32_t)ni, (uint32_t)ni};
+    const uint32_t total = 2u * ((uint32_t)no + (uint32_t)ni);
+    static IdChunk chunk;  // one caller at a time
+    uint32_t done = 0, list = 0, at = 0;
+    while (done < total) {
+        uint32_t n = 0;
+        while (n < kIdsPerLaunch && list < 4) {
+            const uint32_t take = std::min(kIdsPerLaunch - n, len[list] - at);
+            if (take) memcpy(chunk.v + n, src[list] + at, (size_t)take * sizeof(int32_t));
+            n += take;
+            at += take;
+            if (at == len[list]) { list++; at = 0; }
+        }
+        hipLaunchKernelGGL(kv_ids_kernel, dim3(1), dim3(256), 0, s, chunk, ids + done, n,
+                           done == 0 ? p.claim : (unsigned int *)nullptr);
+        HIPTRY((kv_engine *)nullptr, hipGetLastError());
+        done += n;
+    }
+    launch_move(sh.u, e->vec, sh.wgs, sh.lanes, s, p,
+                MoveIds{ids, ids + no, ids + 2 * (size_t)no, ids + 2 * (size_t)no + ni}, true);
+    HIPTRY((kv_engine *)nullptr, hipGetLastError());
+    return KV_OK;
+}
+
 int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d, double *d2h_duplex,
                   double *h2d_duplex)
 {
@@ -1243,6 +1435,7 @@ const char *kv_strerror(int code)
     case KV_EUNSUP: return "path cannot serve this shape or request";
     case KV_EBUSY: return "block or slot still in use by an un-waited call on the other stream";
     case KV_ENOSPC: return "not enough free HBM blocks or host slots";
+    case KV_E2BIG: return "more blocks than the allocation-free entry point's scratch array holds";
     default: return "unknown code";
     }
 }

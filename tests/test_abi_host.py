@@ -27,16 +27,16 @@ def test_every_declared_symbol_is_exported():
 
 def test_codes_match_header_and_oracle():
     text = open(os.path.join(ROOT, "include", "duplexkv.h")).read()
-    codes = {k: int(v) for k, v in re.findall(r"#define\s+(KV_E?[A-Z]+)\s+\(?(-?\d+)\)?", text)}
+    codes = {k: int(v) for k, v in re.findall(r"#define\s+(KV_E?[A-Z0-9]+)\s+\(?(-?\d+)\)?", text)}
     for name in ("KV_OK", "KV_EINVAL", "KV_ERANGE", "KV_EDUP", "KV_EOVERLAP", "KV_ENOMEM",
-                 "KV_EHIP", "KV_EUNSUP", "KV_ENOSPC", "KV_EBUSY"):
+                 "KV_EHIP", "KV_EUNSUP", "KV_ENOSPC", "KV_EBUSY", "KV_E2BIG"):
         assert codes[name] == getattr(B, name)
     assert (B.KV_OK, B.KV_EINVAL, B.KV_ERANGE, B.KV_EDUP, B.KV_EOVERLAP, B.KV_ENOSPC) == \
            (O.OK, O.EINVAL, O.ERANGE, O.EDUP, O.EOVERLAP, O.ENOSPC)
     states = {k: int(v) for k, v in re.findall(r"#define\s+(KV_BLOCK_[A-Z]+)\s+(\d+)", text)}
     assert (states["KV_BLOCK_DIRTY"], states["KV_BLOCK_FULL"], states["KV_BLOCK_SYNCED"], states["KV_BLOCK_HOST"]) == \
            (O.DIRTY, O.FULL, O.SYNCED, O.HOST) == (B.KV_BLOCK_DIRTY, B.KV_BLOCK_FULL, B.KV_BLOCK_SYNCED, B.KV_BLOCK_HOST)
-    for c in range(-9, 1):
+    for c in range(-10, 1):
         assert B.kv_strerror(c) != "unknown code"
     assert B.kv_strerror(-99) == "unknown code"
 
