@@ -22,12 +22,46 @@ if ROOT not in sys.path:
 PCIE5_X16_PER_DIR_GBPS = 64.0   # 32 GT/s x 16 lanes / 8, raw, per direction
 HBM_PEAK_GBPS = 8000.0
 
-# Bytes through L2<->fabric per launch of the dominant kernel, from rocprofv3
-# --pmc FETCH_SIZE and WRITE_SIZE runs of this script, scaled by the plain copy
-# of --calibrate-copy (profiles/kv_move_kernel_llama3_8b.txt).  The counters see
-# HBM and host-memory accesses alike: each moved byte is read once and written
-# once, so the algorithmic figure is 2 x (bytes_out + bytes_in).
-MEASURED_TRAFFIC_BYTES = {("llama3_8b", "fused"): 1076053444}
+
+
+def measured_traffic(workload, path, kernel):
+    """Bytes through L2<->fabric per launch of `kernel`, from rocprofv3 --pmc
+    FETCH_SIZE and WRITE_SIZE runs of this script scaled by the plain copy of
+    --calibrate-copy.  The summaries under profiles/ carry one line per figure,
+        bench-traffic workload=<w> path=<p> kernel=<k> bytes_per_launch=<n>
+    and this looks the line up; (None, None) when no summary covers the run.
+    The counters see HBM and host-memory accesses alike: each moved byte is read
+    once and written once, so the algorithmic figure of the move kernel is
+    2 x (bytes_out + bytes_in)."""
+    pdir = os.path.join(ROOT, "profiles")
+    want = {"workload": workload, "path": path, "kernel": kernel}
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith((".txt", ".md")):
+            continue
+        for line in open(os.path.join(pdir, name)):
+            if not line.startswith("bench-traffic "):
+                continue
+            kv = dict(f.split("=", 1) for f in line.split()[1:] if "=" in f)
+            if all(kv.get(k) == v for k, v in want.items()) and kv.get("bytes_per_launch", "").isdigit():
+                return int(kv["bytes_per_launch"]), "profiles/" + name
+    return None, None
+
+
+def host_topology():
+    """NUMA nodes with their CPU lists, and the CPUs this process may run on."""
+    nodes = {}
+    base = "/sys/devices/system/node"
+    try:
+        for d in sorted(os.listdir(base)):
+            if d.startswith("node") and d[4:].isdigit():
+                nodes[d] = open(os.path.join(base, d, "cpulist")).read().strip()
+    except OSError:
+        pass
+    try:
+        allowed = sorted(os.sched_getaffinity(0))
+    except AttributeError:
+        allowed = list(range(os.cpu_count() or 1))
+    return nodes, allowed
 
 
 def log(*a):
@@ -55,7 +89,8 @@ def cpu_baseline(shape, rot, layout, budget_s=12.0):
     inv = rot.inverse()
     moved = (len(rot.out_ids) + len(rot.in_ids)) * blk
     out = {}
-    for label, threads in (("single", 0), ("all", os.cpu_count() or 1)):
+    nodes, allowed = host_topology()
+    for label, threads in (("single", 0), ("all", len(allowed))):
         for r in (rot, inv):  # warm
             O.rotate(s, hbm, pool, r.out_ids, r.out_slots, r.in_ids, r.in_slots, threads=threads)
         n, t0 = 0, time.perf_counter()
@@ -69,7 +104,8 @@ def cpu_baseline(shape, rot, layout, budget_s=12.0):
     return {"value": round(out["all"][0], 2), "unit": "GB/s", "cores": out["all"][2], "kind": "oracle",
             "sample": f"{out['all'][1]} rotations of the same id lists on pageable host arrays "
                       f"({moved >> 20} MiB moved each), threads split the block lists",
-            "single_thread_value": round(out["single"][0], 2)}
+            "single_thread_value": round(out["single"][0], 2),
+            "numa_nodes": nodes, "cpus_allowed": ",".join(map(str, allowed))}
 
 
 def main():
@@ -114,8 +150,14 @@ def main():
 
     # the denominator first, while no other stream exists in the process (streams
     # share a small number of hardware queues; two that share one serialise)
-    link = B.kv_probe_link(256 << 20, 5)
-    log("hipMemcpyAsync pinned 256 MiB: " + ", ".join(f"{k} {v:.2f} GB/s" for k, v in link.items()))
+    # per direction: the best median over 64 MiB, 256 MiB and 1 GiB copies
+    link, link_by_size = {}, {}
+    for mib in (64, 256, 1024):
+        r = B.kv_probe_link(mib << 20, 5)
+        link_by_size[f"{mib}MiB"] = {k: round(v, 2) for k, v in r.items()}
+        log(f"hipMemcpyAsync pinned {mib} MiB: " + ", ".join(f"{k} {v:.2f} GB/s" for k, v in r.items()))
+        for k, v in r.items():
+            link[k] = max(link.get(k, 0.0), v)
 
     t = time.time()
     cache = W.cache_image(shape, W.value_seed(args.workload), device="cuda")
@@ -197,6 +239,8 @@ def main():
         del again
         log("whole cache verified after the timed loop")
 
+    path_name = B.PATH_NAMES[st["path_used"]]
+    traffic, traffic_src = measured_traffic(args.workload, path_name, "kv_move_kernel")
     res = {
         "metric": "duplex KV rotation GB/s (out+in) and % of measured host-link peak",
         "value": round(gbps_out + gbps_in, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps,
@@ -213,6 +257,7 @@ def main():
                    "bytes_out": bytes_out, "bytes_in": bytes_in, "launches_per_step": st["n_launches"]},
         "gbps_out": round(gbps_out, 2), "gbps_in": round(gbps_in, 2),
         "link_peak_memcpy": {k: round(v, 2) for k, v in link.items()},
+        "link_peak_memcpy_by_size": link_by_size,
         "pct_of_peak_out": round(100 * gbps_out / link["d2h"], 1),
         "pct_of_peak_in": round(100 * gbps_in / link["h2d"], 1),
         "roofline": {
@@ -224,7 +269,7 @@ def main():
             "frac_of_measured_memcpy_peak": round((bytes_out + bytes_in) / (kern_ms * 1e6) /
                                                   (link["d2h"] + link["h2d"]), 4),
             "kernel_ms": round(kern_ms, 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, B.PATH_NAMES[st["path_used"]])),
+            "traffic": traffic, "profile": traffic_src,
             "traffic_algorithmic": 2 * (bytes_out + bytes_in),
             "hbm_frac": round((bytes_out + bytes_in) / (kern_ms * 1e6) / HBM_PEAK_GBPS, 5),
         },
@@ -237,12 +282,12 @@ def main():
     assert rc == 0
     rd_ms = float(np.median(pass_ms[1:]))
     rd_bytes = shape.n_hbm_blocks * blk
+    rd_traffic, rd_src = measured_traffic(args.workload, "reader", "kv_reader_kernel")
     res["roofline_hbm_kernel"] = {
         "bound": "hbm", "kernel": "kv_reader_kernel (synthetic decode reader, whole cache per launch)",
         "achieved": round(rd_bytes / (rd_ms * 1e6), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(rd_bytes / (rd_ms * 1e6) / HBM_PEAK_GBPS, 4), "kernel_ms": round(rd_ms, 4),
-        # FETCH_SIZE x 2.000 of profiles/kv_reader_kernel_interference_shape.txt: 1.0022 x algorithmic
-        "traffic": int(rd_bytes * 1.0022), "traffic_algorithmic": rd_bytes,
+        "traffic": rd_traffic, "profile": rd_src, "traffic_algorithmic": rd_bytes,
     }
     eng.kv_destroy()
     del cache

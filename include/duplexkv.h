@@ -134,7 +134,8 @@ int kv_validate(const kv_config *cfg,
 int kv_create(kv_engine **engine, const kv_config *cfg, void *hbm_cache, void *host_pool,
               void *stream_out, void *stream_in);
 
-/* Waits for outstanding work, then frees everything the engine owns. */
+/* Waits for outstanding work, then frees everything the engine owns.  KV_EBUSY,
+ * with nothing done, while a block table created on the engine still exists. */
 int kv_destroy(kv_engine *engine);
 
 /*

@@ -289,7 +289,8 @@ class Engine:
     def kv_destroy(self) -> int:
         if self._h:
             rc = lib.kv_destroy(self._h)
-            self._h = C.c_void_p()
+            if rc != KV_EBUSY:      # refused while a block table is attached: the handle stays valid
+                self._h = C.c_void_p()
             return rc
         return KV_OK
 

@@ -1094,6 +1094,7 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
 int kv_destroy(kv_engine *e)
 {
     if (!e) return KV_EINVAL;
+    if (e->n_tables > 0) return KV_EBUSY;  // a block table still points at this engine
     if (e->s_read) (void)hipStreamSynchronize(e->s_read);
     (void)hipStreamSynchronize(e->s_out);
     (void)hipStreamSynchronize(e->s_in);

@@ -109,6 +109,7 @@ struct kv_engine {
     bool in_dirty = false;                         // stream_in holds work stream_out has not joined
     bool out_dirty = false;                        // stream_out holds work stream_in has not joined
     bool in_after_out = false;                     // block table in use: in-only work waits for earlier out work
+    int n_tables = 0;                              // block tables attached (kv_destroy refuses while any is)
     double t0 = 0;
     kv_stats acc{}, last{};
     int sticky = KV_OK;

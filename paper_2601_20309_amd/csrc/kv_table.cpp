@@ -32,7 +32,47 @@ struct kv_table {
     FreeIds free_hbm, free_slot;
     kv_table_counts cnt{};
     std::vector<int32_t> oi, os, ii, is, held, seen;
+    // What a rotation had before it started, kept until its transfer is accepted:
+    // the free lists, the counters, and every request the call changes.
+    FreeIds undo_hbm, undo_slot;
+    kv_table_counts undo_cnt{};
+    std::vector<std::pair<int32_t, TableReq>> undo_req;
+    std::vector<int32_t> saved;  // per request: 1 if already in undo_req
 };
+
+namespace {
+
+void save_request(kv_table *t, int32_t q)
+{
+    if (t->saved[(size_t)q]) return;
+    t->saved[(size_t)q] = 1;
+    t->undo_req.emplace_back(q, t->req[(size_t)q]);
+}
+
+void begin_undo(kv_table *t)
+{
+    t->undo_hbm = t->free_hbm;
+    t->undo_slot = t->free_slot;
+    t->undo_cnt = t->cnt;
+    t->undo_req.clear();
+}
+
+// ok: forget the saved state; else put everything back as it was.
+void end_undo(kv_table *t, bool ok)
+{
+    for (auto &pr : t->undo_req) {
+        t->saved[(size_t)pr.first] = 0;
+        if (!ok) t->req[(size_t)pr.first] = std::move(pr.second);
+    }
+    t->undo_req.clear();
+    if (!ok) {
+        t->free_hbm.swap(t->undo_hbm);
+        t->free_slot.swap(t->undo_slot);
+        t->cnt = t->undo_cnt;
+    }
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -51,7 +91,9 @@ int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
     for (int32_t i = 0; i < e->cfg.n_hbm_blocks; i++) t->free_hbm.push(i);
     for (int32_t i = 0; i < e->cfg.n_host_slots; i++) t->free_slot.push(i);
     t->seen.assign((size_t)max_requests, 0);
+    t->saved.assign((size_t)max_requests, 0);
     e->in_after_out = true;
+    e->n_tables++;
     *out = t;
     return KV_OK;
 }
@@ -59,7 +101,7 @@ int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
 int kv_table_destroy(kv_table *t)
 {
     if (!t) return KV_EINVAL;
-    t->e->in_after_out = false;
+    if (--t->e->n_tables == 0) t->e->in_after_out = false;
     delete t;
     return KV_OK;
 }
@@ -122,9 +164,11 @@ static void pick_eager(kv_table *t, int32_t budget, std::vector<std::pair<int32_
     }
 }
 
-static void mark_synced(kv_table *t, const std::vector<std::pair<int32_t, size_t>> &picked, size_t first)
+static void mark_synced(kv_table *t, const std::vector<std::pair<int32_t, size_t>> &picked, size_t first,
+                        bool undoable = false)
 {
     for (size_t k = 0; k < picked.size(); k++) {
+        if (undoable) save_request(t, picked[k].first);
         TableReq &r = t->req[(size_t)picked[k].first];
         r.slot[picked[k].second] = t->os[first + k];
         r.state[picked[k].second] = KV_BLOCK_SYNCED;
@@ -188,9 +232,13 @@ static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int
     if (need_slots > (int64_t)t->free_slot.size()) return KV_ENOSPC;
     if (need_hbm > (int64_t)t->free_hbm.size() + drop) return KV_ENOSPC;
 
+    // From here on the table is changed as if the transfer had been accepted;
+    // should the engine refuse it after all, end_undo() puts everything back.
+    begin_undo(t);
     t->oi.clear(); t->os.clear(); t->ii.clear(); t->is.clear(); t->held.clear();
     int64_t n_drop = 0;
     for (int32_t i = 0; i < n_pre; i++) {
+        save_request(t, pre[i]);
         TableReq &r = t->req[(size_t)pre[i]];
         for (size_t b = 0; b < r.hbm.size(); b++) {
             if (r.state[b] == KV_BLOCK_SYNCED) {
@@ -211,6 +259,7 @@ static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int
         r.resident = false;
     }
     for (int32_t i = 0; i < n_res; i++) {
+        save_request(t, res[i]);
         TableReq &r = t->req[(size_t)res[i]];
         for (size_t b = 0; b < r.hbm.size(); b++) {
             const int32_t id = t->free_hbm.top();
@@ -232,13 +281,17 @@ static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int
     std::vector<int32_t> fresh;
     if (eager_budget > 0) {
         pick_eager(t, eager_budget, picked, fresh);
-        mark_synced(t, picked, n_preempt_copies);
+        mark_synced(t, picked, n_preempt_copies, true);
         t->cnt.copied_eager += (int64_t)picked.size();
     }
-    if (n_eager) *n_eager = (int32_t)picked.size();
-    // the table's own bookkeeping guarantees what admission checks; a failure here is a HIP error
-    return kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
-                     (int32_t)t->ii.size());
+    // The table's own bookkeeping guarantees what admission checks, so a refusal
+    // here is a shape the path cannot serve or a HIP error: nothing was enqueued,
+    // and the table goes back to what it was.
+    rc = kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
+                   (int32_t)t->ii.size());
+    end_undo(t, rc == KV_OK);
+    if (n_eager) *n_eager = rc == KV_OK ? (int32_t)picked.size() : 0;
+    return rc;
 }
 
 int kv_table_rotate(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res)

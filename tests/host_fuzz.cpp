@@ -67,6 +67,10 @@ namespace {
 uint64_t g_block_bytes = 0;
 std::vector<uint8_t> g_hbm, g_pool;
 int64_t g_transfers = 0;
+// When not KV_OK: the next transfer call is refused with this code and moves nothing
+// (an engine failure after the table has done its bookkeeping).
+int g_fail_next = KV_OK;
+int64_t g_refused = 0;
 
 void check_list(const int32_t *a, int32_t n, int32_t limit, std::vector<int> &mark, int bit)
 {
@@ -82,6 +86,12 @@ void check_list(const int32_t *a, int32_t n, int32_t limit, std::vector<int> &ma
 extern "C" int kv_rotate(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
                          const int32_t *is, int32_t ni)
 {
+    if (g_fail_next != KV_OK) {
+        const int rc = g_fail_next;
+        g_fail_next = KV_OK;
+        g_refused++;
+        return rc;
+    }
     std::vector<int> mb((size_t)e->cfg.n_hbm_blocks, 0), ms((size_t)e->cfg.n_host_slots, 0);
     check_list(oi, no, e->cfg.n_hbm_blocks, mb, 1);
     check_list(ii, ni, e->cfg.n_hbm_blocks, mb, 2);
@@ -207,11 +217,22 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
             op = "eager";
             const int32_t budget = (int32_t)(rng() % 9) - (rng() % 53 == 0);
             int32_t ln = -7, on = -7;
+            const bool inject = rng() % 20 == 0;
+            const int64_t refused = g_refused;
+            if (inject) g_fail_next = KV_EHIP;
             const int rl = kv_table_eager(p.lib, budget, &ln);
-            const int ro = okvt_eager(p.ora, p.o_hbm.data(), p.o_pool.data(), budget, &on);
-            CHECK(rl == ro, "step %ld eager(%d): %d, oracle %d", step, budget, rl, ro);
-            if (rl == KV_OK) CHECK(ln == on, "step %ld eager: %d copied, oracle %d", step, ln, on);
-            else failed_ops++;
+            g_fail_next = KV_OK;
+            if (g_refused != refused) {
+                // the engine refused the copies: the table must be what it was (the oracle never hears of it)
+                op = "eager, transfer refused";
+                CHECK(rl == KV_EHIP, "step %ld eager with a refused transfer returned %d", step, rl);
+                failed_ops++;
+            } else {
+                const int ro = okvt_eager(p.ora, p.o_hbm.data(), p.o_pool.data(), budget, &on);
+                CHECK(rl == ro, "step %ld eager(%d): %d, oracle %d", step, budget, rl, ro);
+                if (rl == KV_OK) CHECK(ln == on, "step %ld eager: %d copied, oracle %d", step, ln, on);
+                else failed_ops++;
+            }
         } else if (pick < 90) {
             op = "rotate";
             // random subsets, usually of the right kind, sometimes not
@@ -226,7 +247,28 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
             if (rng() % 150 == 0 && !pre.empty()) res.push_back(pre[0]);  // named twice
             if (rng() % 150 == 0) pre.push_back(max_req + 3);             // out of range
             int rl, ro;
-            if (rng() % 2) {
+            if (rng() % 16 == 0) {
+                // The engine refuses the transfer after the table has worked out the whole
+                // rotation: every mapping, state, free list and counter must be as before.
+                op = "rotate, transfer refused";
+                const int64_t refused = g_refused;
+                const int code = rng() % 2 ? KV_EHIP : KV_EUNSUP;
+                g_fail_next = code;
+                int32_t ln = -7;
+                if (rng() % 2)
+                    rl = kv_table_rotate(p.lib, pre.data(), (int32_t)pre.size(), res.data(), (int32_t)res.size());
+                else
+                    rl = kv_table_rotate_eager(p.lib, pre.data(), (int32_t)pre.size(), res.data(),
+                                               (int32_t)res.size(), (int32_t)(rng() % 7), &ln);
+                g_fail_next = KV_OK;
+                if (g_refused != refused) {
+                    CHECK(rl == code, "step %ld: refused transfer came back as %d", step, rl);
+                    CHECK(ln == -7 || ln == 0, "step %ld: %d eager copies reported for a refused transfer", step, ln);
+                } else {
+                    CHECK(rl != KV_OK, "step %ld: a rotation succeeded without asking the engine", step);
+                }
+                ro = rl;  // the oracle is not told: its table is the "before" the library must still equal
+            } else if (rng() % 2) {
                 rl = kv_table_rotate(p.lib, pre.data(), (int32_t)pre.size(), res.data(), (int32_t)res.size());
                 ro = okvt_rotate(p.ora, p.o_hbm.data(), p.o_pool.data(), pre.data(), (int32_t)pre.size(), res.data(),
                                  (int32_t)res.size());
@@ -264,6 +306,7 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
                 c.swapped_in);
     CHECK(c.copied_eager > 0 && c.copied_preempt > 0 && c.dropped_synced > 0 && c.swapped_in > 0,
           "the fuzz never reached one of the four kinds of block movement");
+    CHECK(g_refused > 0, "the fuzz never refused a transfer");
     CHECK(kv_table_destroy(p.lib) == KV_OK, "destroy");
     okvt_destroy(p.ora);
     return failed_ops;

@@ -134,6 +134,17 @@ def test_eager_rotation_lifecycle(layout):
     s.close()
 
 
+def test_engine_outlives_its_table():
+    sh = W.KVShape(1, 1, 64, 4, n_hbm_blocks=4, n_host_slots=4)
+    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST)
+    s.append(0, 6)
+    assert s.eng.kv_destroy() == B.KV_EBUSY          # refused: the table still points at the engine
+    assert s.rotate([0], []) == 0                    # and both still work
+    s.check()
+    assert s.gt.kv_table_destroy() == 0
+    assert s.eng.kv_destroy() == 0
+
+
 def test_race_rule_on_the_gpu():
     sh = W.KVShape(1, 1, 64, 4, n_hbm_blocks=4, n_host_slots=16)
     s = BothSides(sh, B.KV_HOST_BLOCK_FIRST)
