@@ -165,6 +165,9 @@ int kv_swap_in(kv_engine *engine, const int32_t *host_slots, const int32_t *bloc
  * default path with both lists non-empty) is ordered after everything enqueued
  * before it and before everything enqueued after it, so such rotations can
  * follow one another, over the same blocks too, without a wait.
+ * The id lists of calls in flight live in a ring of 8 descriptor sets: the
+ * ninth call without a kv_wait() in between blocks the host until the oldest of
+ * them has finished on the GPU (so do kv_swap_out / kv_swap_in).
  */
 int kv_rotate(kv_engine *engine,
               const int32_t *out_block_ids, const int32_t *out_host_slots, int32_t n_out,
@@ -228,6 +231,12 @@ int kv_probe_link(uint64_t bytes, int32_t reps, double *d2h, double *h2d,
  * be up to twice n_hbm_blocks).  Read only.  Needs segments that are multiples of 16 bytes (KV_EUNSUP otherwise).
  * max_wgs caps its persistent workgroups (0 = engine picks).  One reader at a time:
  * kv_reader_wait() must come before the next kv_reader_start().
+ * The reader is not ordered against transfers and takes no part in the
+ * KV_EBUSY bookkeeping: a block that a swap-in overwrites while a pass reads it
+ * enters the sum with old, new or mixed bytes (nothing else is affected, the
+ * reader writes nothing to the cache).  A caller who wants a defined sum names
+ * blocks no un-waited swap-in targets, as a decode step only attends over
+ * requests that are resident.
  */
 int kv_reader_start(kv_engine *engine, const int32_t *block_ids, int32_t n, int32_t passes, int32_t max_wgs);
 
@@ -317,8 +326,10 @@ int kv_table_rotate(kv_table *table, const int32_t *preempt, int32_t n_preempt, 
 int kv_table_rotate_eager(kv_table *table, const int32_t *preempt, int32_t n_preempt, const int32_t *resume,
                           int32_t n_resume, int32_t eager_budget, int32_t *n_eager);
 
-/* The request is done: its HBM blocks and host slots are free again (the
- * caller makes sure no transfer of them is still in flight). */
+/* The request is done: its HBM blocks and host slots are free again.  If
+ * transfers the table enqueued are still in flight the call first waits for
+ * them (they may be reading these blocks), so it can block the host; it does
+ * not close the interval kv_last_stats() reports. */
 int kv_table_finish(kv_table *table, int32_t req);
 
 /* Mapping of a request: per block HBM id (-1 if none), host slot (-1 if

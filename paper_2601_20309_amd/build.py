@@ -49,6 +49,22 @@ def build(force: bool = True, verbose: bool = False) -> str:
     return LIB
 
 
+PROBE_SRC = os.path.join(CSRC, "pack_probe.hip")
+PROBE_BIN = os.path.join(HERE, "pack_probe")
+
+
+def build_probe(out: str = PROBE_BIN) -> str:
+    """The stand-alone measurement program that compares shapes of pack / unpack kernel
+    (`python -m paper_2601_20309_amd.experiments packshapes` runs it)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wall", "-Wextra",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-o", out, PROBE_SRC]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("building pack_probe failed:\n" + r.stderr)
+    return out
+
+
 EXAMPLE_SRC = os.path.join(ROOT, "examples", "duplex_demo.c")
 EXAMPLE_BIN = os.path.join(ROOT, "examples", "duplex_demo")
 

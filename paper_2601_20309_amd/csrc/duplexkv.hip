@@ -346,12 +346,30 @@ LinkShape link_shape(const kv_engine *e, LinkKind kind)
     return s;
 }
 
-// HBM-bound pack / unpack launches want the whole chip.
-int pack_wgs(const kv_engine *e)
+// HBM-bound pack / unpack launches.  Measured on one 256 MiB chunk of scattered
+// 32 KiB segments (bare kernel time, source in no cache): persistent waves that
+// loop over 4 KiB tiles, 2048 workgroups, 93 us; one 4 KiB tile per wave (16384
+// workgroups) 89 us; one 1 KiB tile per wave and no loop at all (65536
+// workgroups of 4 waves, dealt out by the hardware dispatcher) 86 us = 78 % of
+// the HBM peak, against 100 us for the runtime's own device copy of that size.
+// The general move kernel pays too much per wave for tiles that small, so this
+// shape has a kernel of its own (kv_stage_kernel).  A configured max_copy_wgs (a
+// copy that has to stay small beside other kernels) keeps that many persistent
+// workgroups of the move kernel with 4 KiB tiles.
+template <bool UNPACK>
+void launch_stage(int vec, hipStream_t s, const dkv::StageParams &p, const int32_t *ids)
 {
-    int w = 8 * (e->n_cus > 0 ? e->n_cus : 256);
-    if (e->cfg.max_copy_wgs > 0) w = std::min(w, (int)e->cfg.max_copy_wgs);
-    return std::max(w, 1);
+    const uint32_t waves_per_wg = dkv::kThreads / dkv::kWave;
+    dim3 g((p.tiles + waves_per_wg - 1) / waves_per_wg), b(dkv::kThreads);
+#define DKV_STAGE(V) hipLaunchKernelGGL((dkv::kv_stage_kernel<V, UNPACK>), g, b, 0, s, p, ids)
+    switch (vec) {
+    case 16: DKV_STAGE(dkv::u32x4); break;
+    case 8: DKV_STAGE(dkv::u32x2); break;
+    case 4: DKV_STAGE(unsigned int); break;
+    case 2: DKV_STAGE(unsigned short); break;
+    default: DKV_STAGE(unsigned char); break;
+    }
+#undef DKV_STAGE
 }
 
 // ---- FUSED / ZEROCOPY -----------------------------------------------------
@@ -411,7 +429,7 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         p_rest.in = none;
         if (!desc(p, no_paired, p.out) || !desc(p, ni, p.in) || !desc(p_rest, n_rest, p_rest.out)) return KV_EUNSUP;
         // in list longer: spread the out tiles over it instead of pairing 1:1
-        if (p.full_tiles && p.in.tiles > p.out.tiles)
+        if (p.in.tiles > p.out.tiles)
             p.mix_q = (((uint64_t)p.out.tiles << 32) + p.in.tiles - 1) / p.in.tiles;
         if (e->in_dirty || !e->own_streams) {
             HIPTRY(e, hipEventRecord(e->ev_join, e->s_in));
@@ -680,6 +698,31 @@ MoveParams stage_params(const kv_engine *e, uint8_t *stage, uint32_t nb, uint32_
     return p;
 }
 
+// The same chunk for kv_stage_kernel; false if it has too many tiles for a 32-bit index.
+bool stage_kernel_params(const kv_engine *e, uint8_t *stage, uint32_t nb, uint32_t p0, uint32_t np,
+                         dkv::StageParams &q)
+{
+    q = dkv::StageParams{};
+    q.hbm = e->hbm;
+    q.stage = stage;
+    hbm_strides(e, q.hbm_plane_stride, q.hbm_block_stride);
+    if (e->cfg.host_layout == KV_HOST_BLOCK_FIRST) {
+        q.slot_stride = (uint64_t)np * e->seg;
+        q.plane_stride = e->seg;
+        q.plane_major = 0;
+    } else {
+        q.slot_stride = e->seg;
+        q.plane_stride = (uint64_t)nb * e->seg;
+        q.plane_major = 1;
+    }
+    q.plane0 = p0;
+    q.n_planes = np;
+    q.n = nb;
+    q.vec_per_seg = (uint32_t)(e->seg / (uint64_t)e->vec);
+    q.tiles_per_seg = (q.vec_per_seg + dkv::kWave - 1) / dkv::kWave;
+    return dir_tiles(nb, np, q.tiles_per_seg, q.tiles);
+}
+
 int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_t no, const int32_t *ii,
                const int32_t *is, int32_t ni)
 {
@@ -687,7 +730,8 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
     int32_t *dd = e->desc_dev + (size_t)k * e->desc_cap;
     int32_t *h_out = dh, *h_in = dh + 2 * (size_t)no;
     int32_t *d_out = dd, *d_in = dd + 2 * (size_t)no;
-    constexpr int U = 4;
+    constexpr int U = 4;                         // capped launches: persistent waves, 4 KiB tiles
+    const int cap_wgs = e->cfg.max_copy_wgs;     // 0: one wave per 1 KiB tile, kv_stage_kernel
     ChunkPlan po{}, pi{};
     if (no > 0) {
         int rc = plan_chunks(e, (uint32_t)no, po);
@@ -698,6 +742,17 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
         int rc = plan_chunks(e, (uint32_t)ni, pi);
         if (rc != KV_OK) return rc;
         sorted_desc(e, ii, is, ni, h_in);
+    }
+    // every chunk's tile count must fit the kernels' 32-bit index: checked for the
+    // largest chunk of each direction before anything is enqueued
+    {
+        const uint64_t vec_per_seg = e->seg / (uint64_t)e->vec;
+        const uint64_t tile = (uint64_t)dkv::kWave * (cap_wgs > 0 ? U : 1);
+        const uint32_t tiles_per_seg = (uint32_t)((vec_per_seg + tile - 1) / tile);
+        uint32_t unused;
+        if ((no > 0 && !dir_tiles(po.blocks_per_chunk, po.planes_per_chunk, tiles_per_seg, unused)) ||
+            (ni > 0 && !dir_tiles(pi.blocks_per_chunk, pi.planes_per_chunk, tiles_per_seg, unused)))
+            return KV_EUNSUP;
     }
     if (no > 0) {
         HIPTRY(e, hipMemcpyAsync(d_out, h_out, 2 * (size_t)no * sizeof(int32_t), hipMemcpyHostToDevice, e->s_out));
@@ -717,12 +772,17 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
         if (!co.done) {
             const uint32_t j1 = std::min<uint32_t>(co.j0 + po.blocks_per_chunk, (uint32_t)no);
             const uint32_t p1 = std::min<uint32_t>(co.p0 + po.planes_per_chunk, e->n_planes);
-            MoveParams p = stage_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, U);
-            p.out = DirDesc{j1 - co.j0, 0, 1, 0};
-            if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
-            const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.out.tiles);
-            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_out, p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr},
-                        false);
+            if (cap_wgs > 0) {
+                MoveParams p = stage_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, U);
+                p.out = DirDesc{j1 - co.j0, 0, 1, 0};
+                if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles)) return KV_EUNSUP;
+                launch_move(U, e->vec, (int)std::min<uint32_t>((uint32_t)cap_wgs, p.out.tiles), dkv::kThreads, e->s_out,
+                            p, MoveIds{d_out + co.j0, nullptr, nullptr, nullptr}, false);
+            } else {
+                dkv::StageParams q;
+                if (!stage_kernel_params(e, e->stage_out, j1 - co.j0, co.p0, p1 - co.p0, q)) return KV_EUNSUP;
+                launch_stage<false>(e->vec, e->s_out, q, d_out + co.j0);
+            }
             HIPTRY(e, hipGetLastError());
             if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
                 return KV_EHIP;
@@ -736,12 +796,17 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             const uint32_t p1 = std::min<uint32_t>(ci.p0 + pi.planes_per_chunk, e->n_planes);
             if (chunk_copies(e, false, e->stage_in, h_in + ni, ci.j0, j1, ci.p0, p1, e->s_in, n_ops) != KV_OK)
                 return KV_EHIP;
-            MoveParams p = stage_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, U);
-            p.in = DirDesc{j1 - ci.j0, 0, 1, 0};
-            if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
-            const int wgs = (int)std::min<uint32_t>((uint32_t)pack_wgs(e), p.in.tiles);
-            launch_move(U, e->vec, wgs, dkv::kThreads, e->s_in, p, MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr},
-                        false);
+            if (cap_wgs > 0) {
+                MoveParams p = stage_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, U);
+                p.in = DirDesc{j1 - ci.j0, 0, 1, 0};
+                if (!dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles)) return KV_EUNSUP;
+                launch_move(U, e->vec, (int)std::min<uint32_t>((uint32_t)cap_wgs, p.in.tiles), dkv::kThreads, e->s_in, p,
+                            MoveIds{nullptr, nullptr, d_in + ci.j0, nullptr}, false);
+            } else {
+                dkv::StageParams q;
+                if (!stage_kernel_params(e, e->stage_in, j1 - ci.j0, ci.p0, p1 - ci.p0, q)) return KV_EUNSUP;
+                launch_stage<true>(e->vec, e->s_in, q, d_in + ci.j0);
+            }
             HIPTRY(e, hipGetLastError());
             n_ops++;
             ci.p0 = p1;
@@ -954,6 +1019,15 @@ double median(std::vector<double> v)
 }
 
 }  // namespace
+
+int dkv::drain(kv_engine *e)
+{
+    if (!e) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    if (e->out_pending) HIPTRY(e, hipStreamSynchronize(e->s_out));
+    if (e->in_pending) HIPTRY(e, hipStreamSynchronize(e->s_in));
+    return KV_OK;
+}
 
 extern "C" {
 
@@ -1224,7 +1298,7 @@ int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, voi
     if (!dir_tiles(p.out.n, p.n_planes, p.tiles_per_seg, p.out.tiles) ||
         !dir_tiles(p.in.n, p.n_planes, p.tiles_per_seg, p.in.tiles))
         return KV_EUNSUP;
-    if (p.full_tiles && p.out.tiles > 0 && p.in.tiles > p.out.tiles)
+    if (p.out.tiles > 0 && p.in.tiles > p.out.tiles)
         p.mix_q = (((uint64_t)p.out.tiles << 32) + p.in.tiles - 1) / p.in.tiles;
     unsigned char *sc = nullptr;
     rc = static_scratch(sc);

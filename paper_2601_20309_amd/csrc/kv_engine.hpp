@@ -72,6 +72,15 @@ inline bool list_bad(const int32_t *p, int32_t n) { return n < 0 || (n > 0 && !p
 
 }  // namespace dkv
 
+struct kv_engine;
+namespace dkv {
+// Blocks until the transfers enqueued so far are done, without closing the
+// interval kv_last_stats() reports (kv_wait does that).  No-op when nothing is
+// pending.  Defined with the engine; the block table calls it before it hands
+// blocks and slots of a finished request to new owners.
+int drain(kv_engine *e);
+}  // namespace dkv
+
 struct kv_engine {
     kv_config cfg;
     int device = 0;

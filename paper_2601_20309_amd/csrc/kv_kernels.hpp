@@ -94,7 +94,9 @@ struct Job {
     const V *src_o;
     V *dst_o;
     uint32_t do_in, do_out;
-    uint32_t v0;  // this lane's first vector within the segment (range checks of ragged tiles)
+    // this lane's first vector within the segment, per direction (range checks of
+    // ragged tiles; the two differ when the out tiles are spread over the in tiles)
+    uint32_t v0_i, v0_o;
 };
 
 // Step t of a launch.  Normally step t is tile t of the out list and tile t of
@@ -120,7 +122,7 @@ __device__ __forceinline__ Job<V> make_job(const MoveParams &p, const int32_t *_
                                            const int32_t *__restrict__ in_slots, uint32_t t, uint32_t lane)
 {
     constexpr uint32_t tile_vecs = kWave * U, tile_bytes = tile_vecs * (uint32_t)sizeof(V);
-    Job<V> j{nullptr, nullptr, nullptr, nullptr, 0u, 0u, 0u};
+    Job<V> j{nullptr, nullptr, nullptr, nullptr, 0u, 0u, 0u, 0u};
     uint32_t t_out = t;
     if (p.mix_q) {
         const uint64_t a = (uint64_t)t * p.mix_q, b = a + p.mix_q;
@@ -134,7 +136,8 @@ __device__ __forceinline__ Job<V> make_job(const MoveParams &p, const int32_t *_
         j.do_in = t < p.in.tiles ? 1u : 0u;
         j.do_out = t < p.out.tiles ? 1u : 0u;
     }
-    j.v0 = (t % p.tiles_per_seg) * tile_vecs + lane;
+    j.v0_i = (t % p.tiles_per_seg) * tile_vecs + lane;
+    j.v0_o = p.mix_q ? (t_out % p.tiles_per_seg) * tile_vecs + lane : j.v0_i;
     if (j.do_in) {
         uint64_t ho, fo;
         locate(p, p.in, in_ids, in_slots, t, p.far_slot_stride_in, p.far_plane_stride_in, tile_bytes, ho, fo);
@@ -153,44 +156,58 @@ __device__ __forceinline__ Job<V> make_job(const MoveParams &p, const int32_t *_
 
 // Loads of one job: the far-side (host) loads first, they have the long
 // latency; then the HBM loads.  FULL: the segment is a whole number of tiles, no
-// lane is ever out of range, and all loads issue back to back.
-template <typename V, int U, bool FULL>
+// lane is ever out of range, and all loads issue back to back.  In an HBM-bound
+// launch (pack / unpack, !LINK) loads and stores alike are marked non-temporal:
+// nothing a mover touches is touched twice.
+template <typename V, int U, bool LINK, bool FULL>
 __device__ __forceinline__ void job_loads(const MoveParams &p, const Job<V> &j, V (&vi)[U], V (&vo)[U])
 {
     if (j.do_in) {
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || j.v0 + u * kWave < p.vec_per_seg) vi[u] = j.src_i[u * kWave];
+        for (int u = 0; u < U; u++) {
+            if (FULL || j.v0_i + u * kWave < p.vec_per_seg) {
+                if constexpr (LINK) vi[u] = j.src_i[u * kWave];
+                else vi[u] = __builtin_nontemporal_load(j.src_i + u * kWave);
+            }
+        }
     }
     if (j.do_out) {
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || j.v0 + u * kWave < p.vec_per_seg) vo[u] = j.src_o[u * kWave];
+        for (int u = 0; u < U; u++) {
+            if (FULL || j.v0_o + u * kWave < p.vec_per_seg) {
+                if constexpr (LINK) vo[u] = j.src_o[u * kWave];
+                else vo[u] = __builtin_nontemporal_load(j.src_o + u * kWave);
+            }
+        }
     }
 }
 
-// Stores of one job.  LINK: the far side is host memory, and its stores are
-// marked non-temporal: plain stores linger in the write-back L2 and are only
-// pushed out when evicted or when the kernel ends, so the upstream link idles
-// early and a kernel's last megabytes leave while the downstream link idles
-// (measured, 8 + 8 MiB both ways: 237 us plain, 188 us non-temporal).
+// Stores of one job.  Stores to the far side are marked non-temporal, and so
+// are the stores into the cache of an HBM-bound launch (unpack).
+// LINK (far side = host memory): plain stores linger in the write-back L2 and
+// are only pushed out when evicted or when the kernel ends, so the upstream
+// link idles early and a kernel's last megabytes leave while the downstream
+// link idles (measured, 8 + 8 MiB both ways: 237 us plain, 188 us non-temporal).
+// Pack / unpack (both sides HBM), one 256 MiB chunk whose source is in no cache:
+// plain loads and stores 109 us, non-temporal stores 100 us, non-temporal loads
+// and stores 95 us (HIP events around the launch).
 template <typename V, int U, bool LINK, bool FULL>
 __device__ __forceinline__ void job_stores(const MoveParams &p, const Job<V> &j, const V (&vi)[U],
                                            const V (&vo)[U])
 {
     if (j.do_out) {
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            if (FULL || j.v0 + u * kWave < p.vec_per_seg) {
-                if constexpr (LINK) __builtin_nontemporal_store(vo[u], j.dst_o + u * kWave);
-                else j.dst_o[u * kWave] = vo[u];
-            }
-        }
+        for (int u = 0; u < U; u++)
+            if (FULL || j.v0_o + u * kWave < p.vec_per_seg) __builtin_nontemporal_store(vo[u], j.dst_o + u * kWave);
     }
     if (j.do_in) {
 #pragma unroll
-        for (int u = 0; u < U; u++)
-            if (FULL || j.v0 + u * kWave < p.vec_per_seg) j.dst_i[u * kWave] = vi[u];
+        for (int u = 0; u < U; u++) {
+            if (FULL || j.v0_i + u * kWave < p.vec_per_seg) {
+                if constexpr (LINK) j.dst_i[u * kWave] = vi[u];
+                else __builtin_nontemporal_store(vi[u], j.dst_i + u * kWave);
+            }
+        }
     }
 }
 
@@ -227,7 +244,7 @@ __device__ __forceinline__ void run_fixed(const MoveParams &p, const int32_t *__
     V vi[U], vo[U];
     Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
     for (;;) {
-        job_loads<V, U, FULL>(p, cur, vi, vo);
+        job_loads<V, U, LINK, FULL>(p, cur, vi, vo);
         t += n_waves;
         const bool more = t < n_steps;
         Job<V> nxt = cur;
@@ -265,7 +282,7 @@ __device__ __forceinline__ void run_drawn(const MoveParams &p, const int32_t *__
         V vi[U], vo[U];
         Job<V> cur = make_job<V, U>(p, out_ids, out_slots, in_ids, in_slots, t, lane);
         for (;;) {
-            job_loads<V, U, FULL>(p, cur, vi, vo);
+            job_loads<V, U, LINK, FULL>(p, cur, vi, vo);
             // The next step.  At the end of a chunk the pending draw is read: here,
             // where the loads have to be waited for anyway (the draw is older than
             // they are), and before the stores: the vector memory counter retires in
@@ -339,6 +356,49 @@ __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p
         p.claim[0] = 0u;
         p.claim[1] = 0u;
     }
+}
+
+// Pack / unpack of the DMA-staged path when nothing caps the launch: both sides
+// are HBM, so the kernel is bound by HBM bandwidth and wants the plainest shape
+// there is.  One wave moves one tile of 64 vectors (1 KiB at 16-byte vectors)
+// and ends; there are as many waves as tiles and the hardware dispatcher deals
+// them out, four to a workgroup.  No loop, no counters, no second direction;
+// loads and stores are non-temporal (nothing is touched twice).  The staging
+// side is addressed by list index: segment (plane, i) at
+// stage + i * slot_stride + (plane - plane0) * plane_stride.
+struct StageParams {
+    uint8_t *hbm, *stage;
+    uint64_t hbm_plane_stride, hbm_block_stride;
+    uint64_t slot_stride, plane_stride;  // staging
+    uint32_t plane0, n_planes;           // planes this launch covers
+    uint32_t n;                          // blocks
+    uint32_t vec_per_seg, tiles_per_seg; // tiles of 64 vectors
+    uint32_t tiles;                      // n * n_planes * tiles_per_seg
+    uint32_t plane_major;                // tile order: 1 = [plane][i][tile], 0 = [i][plane][tile]
+};
+
+template <typename V, bool UNPACK>
+__global__ __launch_bounds__(kThreads) void kv_stage_kernel(const StageParams p, const int32_t *__restrict__ ids)
+{
+    const uint32_t lane = threadIdx.x & (kWave - 1u);
+    const uint32_t t = blockIdx.x * (kThreads / kWave) + threadIdx.x / kWave;
+    if (t >= p.tiles) return;
+    const uint32_t segidx = t / p.tiles_per_seg, tin = t - segidx * p.tiles_per_seg;
+    uint32_t i, pl;
+    if (p.plane_major) {
+        pl = segidx / p.n;
+        i = segidx - pl * p.n;
+    } else {
+        i = segidx / p.n_planes;
+        pl = segidx - i * p.n_planes;
+    }
+    const uint32_t v = tin * kWave + lane;
+    if (v >= p.vec_per_seg) return;
+    V *in_cache = reinterpret_cast<V *>(p.hbm + (uint64_t)(pl + p.plane0) * p.hbm_plane_stride +
+                                        (uint64_t)(uint32_t)ids[i] * p.hbm_block_stride) + v;
+    V *in_stage = reinterpret_cast<V *>(p.stage + (uint64_t)i * p.slot_stride + (uint64_t)pl * p.plane_stride) + v;
+    if constexpr (UNPACK) __builtin_nontemporal_store(__builtin_nontemporal_load(in_stage), in_cache);
+    else __builtin_nontemporal_store(__builtin_nontemporal_load(in_cache), in_stage);
 }
 
 // Synthetic decode reader: streams every segment of the named blocks, plane by

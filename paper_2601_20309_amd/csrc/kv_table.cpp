@@ -309,6 +309,10 @@ int kv_table_rotate_eager(kv_table *t, const int32_t *pre, int32_t n_pre, const 
 int kv_table_finish(kv_table *t, int32_t rq)
 {
     if (!t || rq < 0 || rq >= t->max_req || !t->req[(size_t)rq].used) return KV_EINVAL;
+    // its blocks and slots go to new owners, who write them at once: transfers
+    // that still read them (an eager copy, a preemption) have to be done first
+    const int rc = dkv::drain(t->e);
+    if (rc != KV_OK) return rc;
     TableReq &r = t->req[(size_t)rq];
     for (size_t b = 0; b < r.hbm.size(); b++) {
         if (r.hbm[b] >= 0) t->free_hbm.push(r.hbm[b]);

@@ -10,13 +10,19 @@
   python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
   python -m paper_2601_20309_amd.experiments sizes         # rotation rate against rotation size
   python -m paper_2601_20309_amd.experiments ratio         # rates against the mix of the two directions
+  python -m paper_2601_20309_amd.experiments chunks        # DMA-staged path against chunk size: what serial chunks cost
+  python -m paper_2601_20309_amd.experiments splitcalls    # configs[2] in one call, in 32 waited calls, in 32 un-waited calls
+  python -m paper_2601_20309_amd.experiments packalone     # pack and unpack kernels with nothing beside them (profiling target)
+  python -m paper_2601_20309_amd.experiments packshapes    # shapes of pack / unpack kernel against the HBM roofline
 
 Each prints a markdown table.  Correctness of every path measured here is
 covered by the GPU tests; these runs only time.
 """
 from __future__ import annotations
 
+import os
 import statistics
+import subprocess
 import sys
 import time
 
@@ -175,9 +181,10 @@ def linksweep():
     segments of one size, by one DMA copy per segment and by the gather / scatter
     kernels; for the copies also the host time to enqueue one against the time
     the link needs for it."""
-    print("\n| segment | copies per direction | per-copy DMA D2H GB/s | H2D GB/s | enqueue us / copy | "
-          "link us / copy at 57 GB/s | kernel D2H GB/s | kernel H2D GB/s | fused both ways GB/s (sum) |")
-    print("|---|---|---|---|---|---|---|---|---|")
+    print("\n| segment | copies per direction | per-copy DMA D2H GB/s | H2D GB/s | both ways at once GB/s (sum) | "
+          "host us to enqueue a copy | device us per copy (one way) | link us / copy at 57 GB/s | kernel D2H GB/s (stores only) | "
+          "kernel H2D GB/s (loads only) | fused both ways GB/s (sum) |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
     total = 256 << 20
     for seg in [4 << 10, 16 << 10, 32 << 10, 64 << 10, 256 << 10, 1 << 20, 4 << 20, 16 << 20, 64 << 20]:
         heads = seg // 4096                       # 16 tokens x heads x 128 dims x 2 bytes
@@ -192,23 +199,30 @@ def linksweep():
         # one DMA copy per segment
         eng = B.Engine(B.make_config(shape, path=B.KV_PATH_NAIVE), cache.data_ptr())
         res = {}
-        for d in ("out", "in"):
+        for d in ("out", "in", "both"):
             ts, enq = [], []
             for i in range(3):
                 torch.cuda.synchronize()
                 t0 = time.perf_counter()
                 if d == "out":
                     assert eng.kv_swap_out(rot.out_ids[:n_naive], rot.out_slots[:n_naive]) == 0
-                else:
+                elif d == "in":
                     assert eng.kv_swap_in(rot.in_slots[:n_naive], rot.in_ids[:n_naive]) == 0
+                else:
+                    assert eng.kv_rotate(rot.out_ids[:n_naive], rot.out_slots[:n_naive], rot.in_ids[:n_naive],
+                                         rot.in_slots[:n_naive]) == 0
                 t1 = time.perf_counter()
                 assert eng.kv_wait() == 0
                 t2 = time.perf_counter()
                 if i:
                     ts.append(t2 - t0); enq.append(t1 - t0)
-            res[d] = (2 * n_naive * seg / statistics.median(ts) / 1e9, statistics.median(enq) / (2 * n_naive) * 1e6)
+            copies = 2 * n_naive * (2 if d == "both" else 1)
+            # (GB/s, host us to enqueue one copy, wall us per copy)
+            res[d] = (copies * seg / statistics.median(ts) / 1e9, statistics.median(enq) / copies * 1e6,
+                      statistics.median(ts) / copies * 1e6)
         eng.kv_destroy()
-        row += [f"{res['out'][0]:.2f}", f"{res['in'][0]:.2f}", f"{(res['out'][1] + res['in'][1]) / 2:.2f}",
+        row += [f"{res['out'][0]:.2f}", f"{res['in'][0]:.2f}", f"{res['both'][0]:.2f}",
+                f"{(res['out'][1] + res['in'][1]) / 2:.2f}", f"{(res['out'][2] + res['in'][2]) / 2:.2f}",
                 f"{seg / 57e9 * 1e6:.2f}"]
         # gather / scatter kernels
         eng = B.Engine(B.make_config(shape), cache.data_ptr())
@@ -281,6 +295,181 @@ def ratio():
         print(f"| {n_out} : {n_in} | {ms:.2f} | {n_out * blk / ms / 1e6:.2f} | {n_in * blk / ms / 1e6:.2f} | "
               f"{(n_out + n_in) * blk / ms / 1e6:.2f} |", flush=True)
     eng.kv_destroy()
+
+
+def chunks(name="long70b"):
+    """What the chunk pipeline of the DMA-staged path costs.  Chunks of one
+    direction run strictly one after the other on that direction's stream (pack,
+    copies, pack, ...), so every chunk adds its pack (or unpack) kernel and the
+    kernel <-> copy hand-overs to the direction's time.  The same 20 + 20 GiB
+    rotation with chunks from 64 MiB to 1 GiB: step time against the number of
+    chunks gives that cost per chunk, i.e. what double-buffered overlap could
+    win back; the DMA engines' own both-ways rate is the ceiling of the path."""
+    shape = W.SHAPES[name]
+    link = B.kv_probe_link(1 << 30, 5)
+    print(f"\nhipMemcpyAsync pinned, 1 GiB: D2H {link['d2h']:.2f}, H2D {link['h2d']:.2f}, both at once "
+          f"{link['d2h_duplex']:.2f} GB/s per direction (the DMA engines' ceiling for this path)\n")
+    cache = _cache(shape)
+    rot = W.config_rotation(name, contiguous_slots=True)
+    print("| path | chunk MiB | chunks per direction | kernels + copies | step ms | GB/s per direction | "
+          "of the DMA both-ways ceiling |")
+    print("|---|---|---|---|---|---|---|")
+    plane_pair = 2 * len(rot.out_ids) * B.kv_seg_bytes(B.make_config(shape))     # one layer of the whole list
+    rows = []
+    plans = [(1, plane_pair // 4), (1, plane_pair // 2), (1, plane_pair), (2, 2 * plane_pair), (4, 4 * plane_pair)]
+    for chunk_layers, staging in plans:
+        eng = B.Engine(B.make_config(shape, B.KV_HOST_LAYER_FIRST, B.KV_PATH_SDMA_STAGED, chunk_layers=chunk_layers,
+                                     staging_bytes=staging), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        calls = _rot_calls(eng, rot)
+
+        def fn(i):
+            assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+        ms, _, _ = _time_calls(eng, fn, 4, warm=2)
+        st = eng.kv_last_stats()
+        n_chunks = len(rot.out_ids) * blk // staging
+        gbps = len(rot.out_ids) * blk / ms / 1e6
+        rows.append((n_chunks, ms))
+        print(f"| DMA staged, layer-first pool, consecutive slots | {staging >> 20} | {n_chunks} | {st['n_launches']} | "
+              f"{ms:.1f} | {gbps:.2f} | {100 * gbps / link['d2h_duplex']:.1f} % |", flush=True)
+        eng.kv_destroy()
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    calls = _rot_calls(eng, W.config_rotation(name))
+
+    def fn(i):
+        assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+    ms, _, _ = _time_calls(eng, fn, 4, warm=2)
+    gbps = len(rot.out_ids) * blk / ms / 1e6
+    print(f"| fused kernel, scattered slots (default) | - | - | {eng.kv_last_stats()['n_launches']} | {ms:.1f} | "
+          f"{gbps:.2f} | {100 * gbps / link['d2h_duplex']:.1f} % |", flush=True)
+    eng.kv_destroy()
+    # least squares: step ms = a + b * chunks
+    xs, ys = [r[0] for r in rows], [r[1] for r in rows]
+    mx, my = sum(xs) / len(xs), sum(ys) / len(ys)
+    b = sum((x - mx) * (y - my) for x, y in zip(xs, ys)) / sum((x - mx) ** 2 for x in xs)
+    a = my - b * mx
+    print(f"\nfit: step ms = {a:.1f} + {b * 1e3:.1f} us x chunks per direction; with one chunk per layer "
+          f"(80 chunks) the serial hand-overs cost {80 * b:.1f} ms = {100 * 80 * b / (a + 80 * b):.1f} % of the step")
+
+
+def splitcalls():
+    """configs[2] (32 requests out, 32 in, lognormal lengths) moved (a) in one call,
+    (b) as 32 calls of one request pair each with a kv_wait after every call,
+    (c) as the same 32 calls enqueued back to back with one kv_wait at the end.
+    (b) holds each call's own imbalance (|out_i - in_i| runs at the one-way rate)
+    and 32 launch-and-wait round trips; what (c) has beyond (b) minus those round
+    trips is lost between launches."""
+    shape = W.SHAPES["batch"]
+    cache = _cache(shape)
+    info = W.batch_rotation(shape, W.BASE_SEED + 102)
+    rot = info["rotation"]; bo_, bi_ = info["bounds_out"], info["bounds_in"]
+    inv = rot.inverse()
+    eng = B.Engine(B.make_config(shape), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    whole = _rot_calls(eng, rot)
+    pairs_f, pairs_b, sizes_ = [], [], []
+    for r in range(len(bo_) - 1):
+        o, i_ = slice(bo_[r], bo_[r + 1]), slice(bi_[r], bi_[r + 1])
+        pairs_f.append(eng.prepare(rot.out_ids[o], rot.out_slots[o], rot.in_ids[i_], rot.in_slots[i_]))
+        pairs_b.append(eng.prepare(inv.out_ids[i_], inv.out_slots[i_], inv.in_ids[o], inv.in_slots[o]))
+        sizes_.append((bo_[r + 1] - bo_[r], bi_[r + 1] - bi_[r]))
+
+    def timed(fn_f, fn_b, reps=8):
+        f, b = [], []
+        for i in range(2 + reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            (fn_b if i & 1 else fn_f)()
+            if i >= 2:
+                (b if i & 1 else f).append((time.perf_counter() - t0) * 1e3)
+        return statistics.median(f), statistics.median(b)
+
+    def one(c):
+        def go():
+            assert c() == 0 and eng.kv_wait() == 0
+        return go
+
+    def each_waited(cs):
+        def go():
+            for c in cs:
+                assert c() == 0 and eng.kv_wait() == 0
+        return go
+
+    def unwaited(cs):
+        def go():
+            for c in cs:
+                assert c() == 0
+            assert eng.kv_wait() == 0
+        return go
+
+    a = timed(one(whole[0]), one(whole[1]))
+    b = timed(each_waited(pairs_f), each_waited(pairs_b))
+    c = timed(unwaited(pairs_f), unwaited(pairs_b))
+    # launch-and-wait round trip of a call that moves one block each way
+    tiny = W.simple_rotation(shape, 1, 1, seed=9)
+    tc = _rot_calls(eng, tiny)
+    t1 = timed(one(tc[0]), one(tc[1]), reps=40)
+    fixed_ms = min(t1) - 2 * blk / 100.7e6
+    so = sum(abs(o - i) for o, i in sizes_)
+    print(f"\n{len(rot.out_ids)} blocks out, {len(rot.in_ids)} in; sum over the 32 pairs of |out_i - in_i| = {so} blocks "
+          f"against |sum out - sum in| = {abs(len(rot.out_ids) - len(rot.in_ids))}; a call that moves one block each "
+          f"way and waits takes {min(t1) * 1e3:.0f} us, of which {fixed_ms * 1e3:.0f} us are not link time\n")
+    print("| how | forward ms (out-heavy) | inverse ms (in-heavy) | launches |")
+    print("|---|---|---|---|")
+    print(f"| one call | {a[0]:.2f} | {a[1]:.2f} | 2 / 1 |")
+    print(f"| 32 calls, each waited for | {b[0]:.2f} | {b[1]:.2f} | |")
+    print(f"| 32 calls back to back, one wait | {c[0]:.2f} | {c[1]:.2f} | {eng.kv_last_stats()['n_launches']} |")
+    print(f"| (each waited) - 32 round trips | {b[0] - 32 * fixed_ms:.2f} | {b[1] - 32 * fixed_ms:.2f} | |")
+    print(f"\nlost between launches, back to back: forward {c[0] - (b[0] - 32 * fixed_ms):+.2f} ms, inverse "
+          f"{c[1] - (b[1] - 32 * fixed_ms):+.2f} ms; lost to per-call imbalance: forward "
+          f"{b[0] - 32 * fixed_ms - a[0]:+.2f} ms, inverse {b[1] - 32 * fixed_ms - a[1]:+.2f} ms", flush=True)
+    eng.kv_destroy()
+
+
+def packalone(name="llama3_8b"):
+    """Pack and unpack kernels of the DMA-staged path with nothing running beside
+    them: swap-outs and swap-ins of configs[1]'s 128 blocks in turn, each waited
+    for.  Meant to run under rocprofv3 --kernel-trace --stats, which gives the
+    kernel durations (both directions at once would put the other direction's
+    copies beside each kernel, and under the profiler those copies are kernels)."""
+    shape = W.SHAPES[name]
+    cache = _cache(shape)
+    rot = W.config_rotation(name, contiguous_slots=True)
+    eng = B.Engine(B.make_config(shape, path=B.KV_PATH_SDMA_STAGED), cache.data_ptr())
+    blk = B.kv_block_bytes(eng.cfg)
+    to, ti = [], []
+    for i in range(44):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if i % 2 == 0:
+            assert eng.kv_swap_out(rot.out_ids, rot.out_slots) == 0
+        else:
+            assert eng.kv_swap_in(rot.out_slots, rot.out_ids) == 0
+        assert eng.kv_wait() == 0
+        if i >= 4:
+            (ti if i % 2 else to).append((time.perf_counter() - t0) * 1e3)
+    # a plain 256 MiB device copy of known size, the reference for scaling the profiler's
+    # FETCH_SIZE / WRITE_SIZE readings
+    a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_()
+    b = torch.empty_like(a)
+    for _ in range(3):
+        b.copy_(a)
+    torch.cuda.synchronize()
+    mb = len(rot.out_ids) * blk
+    print(f"swap-out alone (pack + one DMA copy, {mb >> 20} MiB): {statistics.median(to):.3f} ms = "
+          f"{mb / statistics.median(to) / 1e6:.2f} GB/s; swap-in alone (one DMA copy + unpack): "
+          f"{statistics.median(ti):.3f} ms = {mb / statistics.median(ti) / 1e6:.2f} GB/s", flush=True)
+    eng.kv_destroy()
+
+
+def packshapes():
+    """Runs the stand-alone measurement program csrc/pack_probe.hip (built by
+    paper_2601_20309_amd.build.build_probe) and passes its table through."""
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "pack_probe")
+    if not os.path.exists(exe):
+        sys.exit(f"{exe} is not built: run python -c 'from paper_2601_20309_amd import build; build.build_probe()'")
+    raise SystemExit(subprocess.run([exe]).returncode)
 
 
 def configs():
@@ -538,12 +727,40 @@ def eager():
         eng.kv_destroy()
 
 
+def fit_picks(pre, pri, state, blocks_of, free_hbm, b_xfer, headroom):
+    """Harness policy of the serving loops (not part of the method): which of the
+    requests LVF prioritised really start this iteration.  `room` is what the
+    cache holds once the preempted have left, minus `headroom` blocks kept for
+    the tokens the running batch is about to append; a request needs its blocks
+    plus one to grow into; a rotary request also needs its blocks in swap-in
+    budget, since B_xfer bounds what one iteration swaps (Section 4.2.2).  A
+    request that does not fit is skipped and stays where it is.
+    Returns (admit, resume): waiting requests to prefill, rotary ones to swap in."""
+    admit, resume = [], []
+    room = free_hbm + sum(blocks_of(r) for r in pre) - headroom
+    swap_in_left = b_xfer
+    for r in pri:
+        need = blocks_of(r) + 1
+        if need > room:
+            continue
+        if state[r] == B.KV_REQ_ROTARY:
+            if need - 1 > swap_in_left:
+                continue
+            swap_in_left -= need - 1
+            resume.append(r)
+        else:
+            admit.append(r)
+        room -= need
+    return admit, resume
+
+
 def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slots=16384):
-    """Cross-iteration pipeline (Section 4.3.2) with synthetic traffic: while the
-    GPU "executes" iteration t (the decode reader streams the KV of the running
-    batch plus a weights-sized read), LVF (Algorithm 1) picks what rotates for
-    iteration t+1 and the block table moves it, eager copies included.  Reports
-    how often the rotation outlasted the execution (a stall) and the time split,
+    """Cross-iteration pipeline (Section 4.3.2) with synthetic traffic.  Iteration t
+    "executes" on the GPU (the decode reader streams a weights-sized read on its
+    own stream) while the host prepares iteration t+1: LVF (Algorithm 1) picks
+    what rotates and the block table enqueues the transfer, eager copies
+    included.  An iteration stalls when its preparation (scheduling + transfer,
+    on the host clock from the start of the execution) outlasts the execution:
     the quantities of the paper's Section 5.4 stall paragraph."""
     shape = W.SHAPES["llama3_8b"]                 # blocks of 16 tokens; a small cache so that requests must rotate
     shape = W.KVShape(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
@@ -565,12 +782,13 @@ def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slo
     arrivals = np.cumsum(rng.exponential(1.0 / rps, size=int(rps * seconds * 1.2) + 8))
     prompts = np.clip(np.rint(rng.lognormal(np.log(700), 0.9, size=arrivals.size)), 16, 8192).astype(int)
     outputs = np.clip(np.rint(rng.lognormal(np.log(200), 0.8, size=arrivals.size)), 4, 2048).astype(int)
-    state, t_ref, length, target, ids_of = {}, {}, {}, {}, {}
+    state, t_ref, length, target = {}, {}, {}, {}
     ttft, tbt, first_done = [], [], set()
     free_ids = list(range(4095, -1, -1))
     now, next_arrival, it = 0.0, 0, 0
-    n_stall, t_sched, t_xfer, t_exec, moved_blocks = 0, [], [], [], 0
+    n_stall, n_rot, t_sched, t_xfer, t_prep, t_exec, moved_blocks = 0, 0, [], [], [], [], 0
     arrive_time = {}
+    blocks_of = lambda r: -(-length[r] // P)
     while now < seconds:
         while next_arrival < arrivals.size and arrivals[next_arrival] <= now and free_ids:
             r = free_ids.pop()
@@ -578,73 +796,60 @@ def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slo
             arrive_time[r] = float(arrivals[next_arrival])
             length[r], target[r] = int(prompts[next_arrival]), int(prompts[next_arrival] + outputs[next_arrival])
             next_arrival += 1
-        # ---- host: schedule iteration t+1 -------------------------------------------------------
+        # ---- GPU: iteration t executes ---------------------------------------------------------------
+        batch = [r for r in state if state[r] == B.KV_REQ_RUNNING]
+        x0 = time.perf_counter()
+        assert eng.kv_reader_start(weights_ids, 1) == 0
+        # ---- host, meanwhile: schedule iteration t+1 and enqueue its rotation --------------------------
         h0 = time.perf_counter()
-        reqs = [(r, state[r], -(-length[r] // P), t_ref[r]) for r in state]
+        reqs = [(r, state[r], blocks_of(r), t_ref[r]) for r in state]
         free_hbm = tab.kv_table_get_counts()["free_hbm_blocks"]
         rc, pre, pri, fcfs = B.kv_sched_lvf(params, reqs, now, b_xfer, free_hbm)
         assert rc == 0
-        # leave room for the tokens the running batch is about to append
-        running_after = [r for r in state if state[r] == B.KV_REQ_RUNNING and r not in pre]
-        headroom = len(running_after) + 8
-        admit, resume, room = [], [], free_hbm + sum(-(-length[r] // P) for r in pre) - headroom
-        swap_in_left = b_xfer                     # the budget bounds what one iteration swaps (Section 4.2.2)
-        for r in pri:
-            need = -(-length[r] // P) + 1
-            if need > room:
-                continue
-            if state[r] == B.KV_REQ_ROTARY:
-                if need - 1 > swap_in_left:
-                    continue
-                swap_in_left -= need - 1
-                resume.append(r)
-            else:
-                admit.append(r)
-            room -= need
+        running_after = [r for r in batch if r not in pre]
+        admit, resume = fit_picks(pre, pri, state, blocks_of, free_hbm, b_xfer, headroom=len(running_after) + 8)
         # the eager step rides in the rotation's transfer: swap-out bytes up to ~0.8 x the
         # swap-in bytes cost no link time
-        spent = sum(-(-length[r] // P) for r in resume) + len(pre)
+        spent = sum(blocks_of(r) for r in resume) + len(pre)
         rc, n_eager = tab.kv_table_rotate_eager(pre, resume, max(0, b_xfer - spent))
         if rc == B.KV_ENOSPC:                     # copied-out blocks are not reusable within the call
             resume = []
             rc, n_eager = tab.kv_table_rotate_eager(pre, [], max(0, b_xfer - len(pre)))
         assert rc == 0, B.kv_strerror(rc)
-        c0 = tab.kv_table_get_counts()
+        sched_ms = (time.perf_counter() - h0) * 1e3      # LVF, the fit, the table's work and the enqueue
+        assert eng.kv_wait() == 0
+        prep_ms = (time.perf_counter() - x0) * 1e3       # scheduling + transfer, from the start of the execution
+        st = eng.kv_last_stats()
+        rc, _, pm = eng.kv_reader_wait()
+        assert rc == 0
+        exec_ms = pm[0]
+        moved = (st["bytes_out"] + st["bytes_in"]) // blk
+        moved_blocks += moved
+        t_sched.append(sched_ms)
+        t_exec.append(exec_ms)
+        if moved:
+            n_rot += 1
+            t_xfer.append(st["ms_e2e"])                  # the engine's clock: transfer call entry to kv_wait return
+            t_prep.append(prep_ms)
+            n_stall += prep_ms > exec_ms
+        if fixed_budget is None:
+            b_xfer = max(8, int(0.8 * 48e9 * float(np.mean(t_exec[-32:])) * 1e-3 / blk))
+        now += max(exec_ms, prep_ms) * 1e-3
+        it += 1
+        # ---- bookkeeping of what was decided -----------------------------------------------------------
+        started = []
         for r in admit:
             rc, new = tab.kv_table_append(r, length[r])
             if rc != 0:
                 continue
-            ids_of[r] = list(new)
             state[r], t_ref[r] = B.KV_REQ_RUNNING, now
+            started.append(r)
         for r in pre:
             state[r], t_ref[r] = B.KV_REQ_ROTARY, t_ref.get(("last", r), now)
         for r in resume:
             state[r], t_ref[r] = B.KV_REQ_RUNNING, now
-            ids_of[r] = tab.kv_table_blocks(r)["ids"]
-        t_sched.append((time.perf_counter() - h0) * 1e3)
-        # ---- GPU: execute iteration t while the rotation runs -------------------------------------
-        batch = [r for r in state if state[r] == B.KV_REQ_RUNNING and r not in resume and r not in admit]
-        read_ids = weights_ids
-        x0 = time.perf_counter()
-        assert eng.kv_reader_start(read_ids, 1) == 0
-        assert eng.kv_wait() == 0
-        xfer_ms = (time.perf_counter() - x0) * 1e3
-        rc, _, pm = eng.kv_reader_wait()
-        assert rc == 0
-        exec_ms = pm[0]
-        st = eng.kv_last_stats()
-        moved = (st["bytes_out"] + st["bytes_in"]) // blk
-        moved_blocks += moved
-        if moved:
-            t_xfer.append(xfer_ms)
-            n_stall += xfer_ms > exec_ms
-        t_exec.append(exec_ms)
-        if fixed_budget is None:
-            b_xfer = max(8, int(0.8 * 48e9 * float(np.mean(t_exec[-32:])) * 1e-3 / blk))
-        now += max(exec_ms, xfer_ms if moved else 0.0) * 1e-3 + t_sched[-1] * 1e-3 * 0  # scheduling overlaps execution
-        it += 1
         # ---- every request of the batch (and every admitted prompt) yields one token ----------------
-        for r in batch + admit:
+        for r in batch + started:
             if state.get(r) != B.KV_REQ_RUNNING:
                 continue
             if r not in first_done:
@@ -657,16 +862,14 @@ def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slo
             if length[r] >= target[r]:
                 assert eng.kv_wait() == 0
                 assert tab.kv_table_finish(r) == 0
-                for d in (state, length, target, ids_of):
+                for d in (state, length, target):
                     d.pop(r, None)
                 t_ref.pop(r, None); t_ref.pop(("last", r), None)
                 first_done.discard(r)
                 free_ids.append(r)
                 continue
             rc, new = tab.kv_table_append(r, 1)
-            if rc == 0:
-                ids_of[r].extend(new)
-            else:
+            if rc != 0:
                 length[r] -= 1                    # cache full: the token waits for the next iteration
     # every synced block must still equal its DRAM copy
     assert eng.kv_wait() == 0
@@ -687,11 +890,13 @@ def serve(rps=45.0, seconds=20.0, seed=0, b_xfer=None, hbm_blocks=4096, host_slo
     print(f"\nsynthetic serving, {rps:g} requests/s for {seconds:g} s of virtual time, B_xfer = {b_xfer} blocks "
           f"({b_xfer * blk / 2**20:.0f} MiB) per iteration{'' if fixed_budget is not None else ' (0.8 x link rate x execution time)'}, "
           f"HBM cache {shape.n_hbm_blocks} blocks, {len(state)} requests still in flight\n")
-    print("| iterations | with a rotation | stalled (rotation outlasted execution) | schedule ms avg | transfer ms avg | "
-          "execution ms avg | blocks moved | eager copies | copied at preemption | dropped without copy | swapped in |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|")
-    print(f"| {it} | {len(t_xfer)} | {n_stall} ({100.0 * n_stall / max(it, 1):.2f} % of iterations) | {np.mean(t_sched):.2f} | "
-          f"{np.mean(t_xfer) if t_xfer else 0:.2f} | {np.mean(t_exec):.2f} | {moved_blocks} | {c['copied_eager']} | "
+    print("| iterations | with a rotation | stalled (scheduling + transfer outlasted execution) | schedule ms avg | "
+          "transfer ms avg (engine clock) | schedule + transfer ms avg, p99 | execution ms avg | blocks moved | eager copies | "
+          "copied at preemption | dropped without copy | swapped in |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
+    print(f"| {it} | {n_rot} | {n_stall} ({100.0 * n_stall / max(it, 1):.2f} % of iterations) | {np.mean(t_sched):.2f} | "
+          f"{np.mean(t_xfer) if t_xfer else 0:.2f} | {np.mean(t_prep) if t_prep else 0:.2f}, {q(t_prep, 99):.2f} | "
+          f"{np.mean(t_exec):.2f} | {moved_blocks} | {c['copied_eager']} | "
           f"{c['copied_preempt']} | {c['dropped_synced']} | {c['swapped_in']} |")
     print(f"\nTTFT p50 / p99: {q(ttft, 50):.3f} / {q(ttft, 99):.3f} s over {len(ttft)} requests; "
           f"TBT p50 / p99: {q(tbt, 50) * 1e3:.1f} / {q(tbt, 99) * 1e3:.1f} ms over {len(tbt)} tokens; "
@@ -709,4 +914,5 @@ if __name__ == "__main__":
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
      "linksweep": linksweep, "serve": serve,
-     "sizes": sizes, "ratio": ratio}[what]()
+     "sizes": sizes, "ratio": ratio, "chunks": chunks, "splitcalls": splitcalls, "packalone": packalone,
+     "packshapes": packshapes}[what]()

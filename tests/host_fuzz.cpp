@@ -110,6 +110,9 @@ extern "C" int kv_swap_out(kv_engine *e, const int32_t *ids, const int32_t *slot
     return kv_rotate(e, ids, slots, n, nullptr, nullptr, 0);
 }
 
+// the stand-in's transfers are done when the call returns
+int dkv::drain(kv_engine *) { return KV_OK; }
+
 // ---- table fuzz
 namespace {
 

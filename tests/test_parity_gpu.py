@@ -272,6 +272,25 @@ def test_in_heavy_interleave_for_every_launch_shape(lanes, wgs, u):
         case.close()
 
 
+@pytest.mark.parametrize("hbm_layout", [B.KV_HBM_LAYER_FIRST, B.KV_HBM_BLOCK_FIRST])
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("u", [0, 2, 4])
+def test_in_heavy_interleave_on_ragged_segments(u, layout, hbm_layout):
+    """Segments that are not a whole number of tiles (1200 bytes = 75 vectors, tiles
+    of 64, 128 or 256): the out tiles spread over a longer in list sit at other
+    places of their segments than the in tiles they ride with, so each direction
+    needs its own range check."""
+    sh = W.SHAPES["ragged"]
+    for n_out, n_in in [(1, 12), (5, 12), (6, 12), (2, 3)]:
+        rot = W.simple_rotation(sh, n_out, n_in, seed=n_out * 100 + n_in + u)
+        case, _ = make_case(sh, layout, B.KV_PATH_FUSED, rot=rot, vecs_per_lane=u, hbm_layout=hbm_layout)
+        case.rotate(rot)
+        case.check()
+        case.rotate(rot.inverse())      # out-heavy: pairs 1:1, the rest alone
+        case.check()
+        case.close()
+
+
 def test_racing_calls_are_refused_and_joined_calls_are_not():
     """Un-waited calls run in order per stream and side by side across the two
     streams: a call that would read what un-waited work on the other stream

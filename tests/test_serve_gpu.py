@@ -1,11 +1,100 @@
 """The whole stack in one loop: LVF decides, the block table rotates with eager
-copies, the reader stands in for model execution on its own stream.  Short run
-on a small cache so that requests really rotate."""
+copies, the engine moves the bytes.  First in lock step with the oracle's
+scheduler and table on host images (decisions, mappings, counters and every
+byte compared), then the timed loop of the experiments on a small cache."""
+import numpy as np
 import pytest
 
+from oracle import kv_oracle as O
+from paper_2601_20309_amd import binding as B
 from paper_2601_20309_amd import experiments as X
+from paper_2601_20309_amd import workloads as W
+from tests.test_table_gpu import BothSides
 
 pytestmark = pytest.mark.gpu
+
+PARAMS = (3.0, 0.0, 0.5, 0.1, 5.0)     # alpha, beta_B, beta_F, S_B, S_F of the paper's Section 5.1
+
+
+@pytest.mark.parametrize("seed,path", [(0, B.KV_PATH_AUTO), (1, B.KV_PATH_AUTO), (2, B.KV_PATH_ZEROCOPY)])
+def test_serving_loop_in_lock_step_with_the_oracle(seed, path):
+    """A fixed-budget serving loop on virtual time (Section 4.2.2, Algorithm 1,
+    feeding Section 4.3.2's block table): every iteration both sides schedule,
+    rotate with the eager step riding along, prefill the admitted requests and
+    append one token to every running one.  The library (scheduler + table +
+    engine on the GPU) and the oracle (its scheduler + its table on host images)
+    must take the same decisions and end with the same mappings, counters and
+    bytes.  Which picks fit (fit_picks) and when requests arrive is the
+    harness's policy, computed once and fed to both."""
+    sh = W.KVShape(2, 2, 64, 4, n_hbm_blocks=40, n_host_slots=160)
+    max_req, b_xfer, dt = 10, 12, 0.02
+    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=max_req, seed=seed, path=path)
+    rng = np.random.default_rng(900 + seed)
+    P = sh.block_size
+    state, t_ref, length, target, last = {}, {}, {}, {}, {}
+    now = 0.0
+    seen = dict(fcfs=0, lvf=0, preempted=0, resumed=0, admitted=0, finished=0, eager=0, skipped=0)
+    blocks_of = lambda r: -(-length[r] // P)
+    for it in range(220):
+        # arrivals (harness): up to two new requests while ids are free
+        for _ in range(int(rng.integers(0, 3))):
+            free = [r for r in range(max_req) if r not in state]
+            if free and rng.random() < 0.6:
+                r = int(rng.choice(free))
+                state[r], t_ref[r] = B.KV_REQ_WAITING, now - float(rng.uniform(0, 4))
+                length[r] = int(rng.integers(3, 40))
+                target[r] = length[r] + int(rng.integers(2, 30))
+        # both schedulers on the same queue
+        reqs = [(r, state[r], blocks_of(r), t_ref[r]) for r in sorted(state)]
+        free_o, free_g = s.ot.counts()["free_hbm"], s.gt.kv_table_get_counts()["free_hbm_blocks"]
+        assert free_o == free_g
+        want = O.sched_lvf(PARAMS, reqs, now, b_xfer, free_o)
+        got = B.kv_sched_lvf(PARAMS, reqs, now, b_xfer, free_g)
+        assert got == want, f"iteration {it}: library {got}, oracle {want}"
+        rc, pre, pri, fcfs = got
+        assert rc == 0
+        seen["fcfs" if fcfs else "lvf"] += 1
+        running_after = [r for r in state if state[r] == B.KV_REQ_RUNNING and r not in pre]
+        admit, resume = X.fit_picks(pre, pri, state, blocks_of, free_g, b_xfer, headroom=len(running_after))
+        seen["skipped"] += len(pri) - len(admit) - len(resume)
+        # the rotation with the eager step in one transfer, on both sides
+        spent = sum(blocks_of(r) for r in resume) + len(pre)
+        rc, n_eager = s.rotate_eager(pre, resume, max(0, b_xfer - spent))
+        if rc == B.KV_ENOSPC:
+            resume = []
+            rc, n_eager = s.rotate_eager(pre, [], max(0, b_xfer - len(pre)))
+        assert rc == 0
+        seen["eager"] += n_eager
+        seen["preempted"] += len(pre)
+        seen["resumed"] += len(resume)
+        now += dt
+        for r in pre:
+            state[r], t_ref[r] = B.KV_REQ_ROTARY, last.get(r, now)
+        for r in resume:
+            state[r], t_ref[r] = B.KV_REQ_RUNNING, now
+        # prefill of the admitted requests, one token for every running one (the "model" writes on both sides)
+        for r in admit:
+            if s.append(r, length[r]) == 0:
+                state[r], t_ref[r] = B.KV_REQ_RUNNING, now
+                seen["admitted"] += 1
+        for r in [r for r in sorted(state) if state[r] == B.KV_REQ_RUNNING and r not in resume]:
+            last[r] = now
+            if length[r] + 1 >= target[r]:
+                assert s.finish(r) == 0
+                for d in (state, t_ref, length, target, last):
+                    d.pop(r, None)
+                seen["finished"] += 1
+            elif s.append(r, 1) == 0:
+                length[r] += 1
+        if it % 20 == 19:
+            s.check(max_req)
+    s.check(max_req)
+    c = s.gt.kv_table_get_counts()
+    # the run must have been through every kind of decision and block movement
+    assert seen["fcfs"] > 0 and seen["lvf"] > 0, seen
+    assert seen["preempted"] > 0 and seen["resumed"] > 0 and seen["admitted"] > 0 and seen["finished"] > 0, seen
+    assert c["copied_eager"] > 0 and c["dropped_synced"] > 0 and c["swapped_in"] > 0, c
+    s.close()
 
 
 def test_cross_iteration_pipeline_runs_and_keeps_synced_blocks_valid():
