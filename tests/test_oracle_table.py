@@ -225,6 +225,52 @@ def test_random_schedules_preserve_every_token(layout, seed):
     assert c["copied_eager"] > 0 and c["copied_preempt"] > 0 and c["dropped_synced"] > 0 and c["swapped_in"] > 0
 
 
+def test_rotation_with_eager_step_hand_worked():
+    """okvt_rotate_eager against a result worked out by hand from the rules alone
+    (blocks and slots are always the lowest-numbered free ones; a preempted
+    request copies out what has no DRAM copy; the blocks it copies out are not
+    reusable within the call; the eager step comes after the rotation and visits
+    resident requests by ascending id, blocks by index).  4-token blocks, 16 HBM
+    blocks, 24 slots.
+
+      append(0, 9)      request 0 takes blocks 0 1 2           FULL FULL DIRTY
+      append(1, 8)      request 1 takes blocks 3 4             FULL FULL
+      rotate([1], [])   1 has no DRAM copies: 3 4 -> slots 0 1; blocks 3 4 free again
+      append(2, 14)     request 2 takes blocks 3 4 5 6         FULL FULL FULL DIRTY
+      rotate_eager([0], [1], budget 2)
+        request 0 out:  0 1 2 -> slots 2 3 4 (three copies at preemption, nothing to drop)
+        request 1 in:   slots 0 1 -> blocks 7 8 (0 1 2 are being copied out, 3..6 are in use)
+        eager step:     request 1 is all SYNCED; request 2's first two FULL blocks,
+                        3 and 4, -> slots 5 6 and become SYNCED; the budget is spent
+    """
+    sh = W.KVShape(2, 2, 8, 4, n_hbm_blocks=16, n_host_slots=24)
+    o = OracleSide(sh, O.BLOCK_FIRST, seed=9)
+    assert o.append(0, 9) == [0, 1, 2]
+    assert o.append(1, 8) == [3, 4]
+    o.rotate([1], [])
+    assert o.append(2, 14) == [3, 4, 5, 6]
+    cv = V.hbm_view(sh, o.cache)
+    before = {b: cv[:, :, b].copy() for b in range(7)}
+    pv = V.pool_view(sh, o.pool, O.BLOCK_FIRST)
+    staged = {sl: pv[:, :, sl].copy() for sl in (0, 1)}
+    rc, n = o.t.rotate_eager(o.u8(o.cache), o.u8(o.pool), [0], [1], 2)
+    assert (rc, n) == (O.OK, 2)
+    assert o.t.blocks(0) == dict(ids=[-1, -1, -1], slots=[2, 3, 4], states=[HOST] * 3, len=9, resident=False)
+    assert o.t.blocks(1) == dict(ids=[7, 8], slots=[0, 1], states=[SYNCED] * 2, len=8, resident=True)
+    assert o.t.blocks(2) == dict(ids=[3, 4, 5, 6], slots=[5, 6, -1, -1], states=[SYNCED, SYNCED, FULL, DIRTY],
+                                 len=14, resident=True)
+    assert o.t.counts() == dict(free_hbm=10, free_slots=17, copied_eager=2, copied_preempt=5, dropped_synced=0,
+                                swapped_in=2)
+    # the bytes went where the table says
+    for blk_id, slot in ((0, 2), (1, 3), (2, 4), (3, 5), (4, 6)):
+        assert np.array_equal(pv[:, :, slot], before[blk_id]), f"slot {slot} does not hold block {blk_id}"
+    for slot, blk_id in ((0, 7), (1, 8)):
+        assert np.array_equal(cv[:, :, blk_id], staged[slot]), f"block {blk_id} does not hold slot {slot}"
+    for b in range(7):
+        assert np.array_equal(cv[:, :, b], before[b])      # copies, not moves
+    o.check()
+
+
 def test_rotation_with_the_eager_step_riding_along():
     """Request 0 leaves, request 1 comes back, and request 2, which stays, gets its
     full blocks copied out in the same call: counted as eager copies, SYNCED
