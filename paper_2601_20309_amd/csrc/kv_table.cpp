@@ -3,9 +3,9 @@
 // translation of "these requests leave, those come back" into one duplex
 // transfer.  Host code only; every byte is moved by the engine's paths.
 #include <algorithm>
-#include <functional>
+#include <cstdint>
 #include <new>
-#include <queue>
+#include <utility>
 #include <vector>
 
 #include "kv_engine.hpp"
@@ -20,8 +20,72 @@ struct TableReq {
     std::vector<int32_t> hbm, slot, state;
 };
 
-// ids that are free, lowest first
-using FreeIds = std::priority_queue<int32_t, std::vector<int32_t>, std::greater<int32_t>>;
+// The ids that are free, handed out lowest first.  One bit per id, plus one bit
+// per 64-id word that says "this word has a free id", so that the lowest free id
+// is two scans of a few words (a 288 GB cache of 2 MiB blocks is 2200 words and
+// 35 summary words).  While a journal is open every change is noted and can be
+// taken back, which is how a rotation the engine refuses is undone without
+// copying the set.
+class FreeIds {
+  public:
+    void reset(int32_t n)
+    {
+        bits_.assign(((size_t)n + 63) / 64, 0);
+        any_.assign((bits_.size() + 63) / 64, 0);
+        count_ = 0;
+        journal_.clear();
+        open_ = false;
+    }
+    size_t size() const { return count_; }
+    bool empty() const { return count_ == 0; }
+    void push(int32_t id) { flip(id, true); }
+    // lowest free id; the set must not be empty
+    int32_t top() const
+    {
+        for (size_t a = 0; a < any_.size(); a++) {
+            if (!any_[a]) continue;
+            const size_t w = a * 64 + (size_t)__builtin_ctzll(any_[a]);
+            return (int32_t)(w * 64 + (size_t)__builtin_ctzll(bits_[w]));
+        }
+        return -1;
+    }
+    void pop() { flip(top(), false); }
+    void open_journal()
+    {
+        journal_.clear();
+        open_ = true;
+    }
+    // keep = false: every change since open_journal() is taken back, latest first
+    void close_journal(bool keep)
+    {
+        open_ = false;
+        if (!keep)
+            for (size_t k = journal_.size(); k-- > 0;) flip(journal_[k].first, !journal_[k].second);
+        journal_.clear();
+    }
+
+  private:
+    void flip(int32_t id, bool to_free)
+    {
+        const size_t w = (size_t)id / 64;
+        const uint64_t m = 1ull << ((size_t)id % 64);
+        if (to_free == ((bits_[w] & m) != 0)) return;  // already so
+        if (to_free) {
+            bits_[w] |= m;
+            any_[w / 64] |= 1ull << (w % 64);
+            count_++;
+        } else {
+            bits_[w] &= ~m;
+            if (!bits_[w]) any_[w / 64] &= ~(1ull << (w % 64));
+            count_--;
+        }
+        if (open_) journal_.emplace_back(id, to_free);
+    }
+    std::vector<uint64_t> bits_, any_;
+    size_t count_ = 0;
+    std::vector<std::pair<int32_t, bool>> journal_;  // (id, became free)
+    bool open_ = false;
+};
 
 }  // namespace
 
@@ -33,8 +97,7 @@ struct kv_table {
     kv_table_counts cnt{};
     std::vector<int32_t> oi, os, ii, is, held, seen;
     // What a rotation had before it started, kept until its transfer is accepted:
-    // the free lists, the counters, and every request the call changes.
-    FreeIds undo_hbm, undo_slot;
+    // the counters and every request the call changes (the free sets keep a journal).
     kv_table_counts undo_cnt{};
     std::vector<std::pair<int32_t, TableReq>> undo_req;
     std::vector<int32_t> saved;  // per request: 1 if already in undo_req
@@ -51,8 +114,8 @@ void save_request(kv_table *t, int32_t q)
 
 void begin_undo(kv_table *t)
 {
-    t->undo_hbm = t->free_hbm;
-    t->undo_slot = t->free_slot;
+    t->free_hbm.open_journal();
+    t->free_slot.open_journal();
     t->undo_cnt = t->cnt;
     t->undo_req.clear();
 }
@@ -65,11 +128,9 @@ void end_undo(kv_table *t, bool ok)
         if (!ok) t->req[(size_t)pr.first] = std::move(pr.second);
     }
     t->undo_req.clear();
-    if (!ok) {
-        t->free_hbm.swap(t->undo_hbm);
-        t->free_slot.swap(t->undo_slot);
-        t->cnt = t->undo_cnt;
-    }
+    t->free_hbm.close_journal(ok);
+    t->free_slot.close_journal(ok);
+    if (!ok) t->cnt = t->undo_cnt;
 }
 
 }  // namespace
@@ -88,6 +149,8 @@ int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
     t->e = e;
     t->max_req = max_requests;
     t->req.resize((size_t)max_requests);
+    t->free_hbm.reset(e->cfg.n_hbm_blocks);
+    t->free_slot.reset(e->cfg.n_host_slots);
     for (int32_t i = 0; i < e->cfg.n_hbm_blocks; i++) t->free_hbm.push(i);
     for (int32_t i = 0; i < e->cfg.n_host_slots; i++) t->free_slot.push(i);
     t->seen.assign((size_t)max_requests, 0);
