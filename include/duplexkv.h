@@ -193,7 +193,10 @@ int kv_rotate(kv_engine *engine,
  * other (the same stream, or streams the caller orders): two calls that overlap
  * in time race on the id lists.  One host thread at a time, process-wide.  No
  * KV_EBUSY tracking: ordering against other work on the same blocks is the
- * stream's order.
+ * stream's order.  The call may be recorded into a HIP graph (stream capture)
+ * once one call on that device has been made outside any capture (the first
+ * call looks up the array's device address); the id lists are then part of the
+ * recording, and a replay moves what the blocks and slots hold at that moment.
  */
 #define KV_STATIC_MAX_BLOCKS 8192
 int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, void *stream,

@@ -259,87 +259,109 @@ int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
     return KV_OK;
 }
 
+// Are the named requests known, named once, and where the call needs them
+// (resident to leave, in DRAM to come back)?
+static bool names_ok(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res)
+{
+    bool ok = true;
+    auto claim = [&](int32_t q, bool want_resident) {
+        if (q < 0 || q >= t->max_req) return false;
+        const TableReq &r = t->req[(size_t)q];
+        if (!r.used || r.resident != want_resident || t->seen[(size_t)q]) return false;
+        t->seen[(size_t)q] = 1;
+        return true;
+    };
+    int32_t marked_pre = 0, marked_res = 0;  // entries claimed so far
+    while (ok && marked_pre < n_pre) {
+        ok = claim(pre[marked_pre], true);
+        if (ok) marked_pre++;
+    }
+    while (ok && marked_res < n_res) {
+        ok = claim(res[marked_res], false);
+        if (ok) marked_res++;
+    }
+    for (int32_t i = 0; i < marked_pre; i++) t->seen[(size_t)pre[i]] = 0;
+    for (int32_t i = 0; i < marked_res; i++) t->seen[(size_t)res[i]] = 0;
+    return ok;
+}
+
+// A request leaves HBM.  Blocks with a valid DRAM copy are released on the spot,
+// without a byte moving, and may be refilled by this very call; the others join
+// the out list (taking the lowest free slot if they have none) and stay out of
+// the free set until the call's swap-ins have been placed, because a block this
+// call still reads must not be one it writes.  False: the pool has no slot left.
+static bool leave_hbm(kv_table *t, int32_t q, int64_t &released)
+{
+    save_request(t, q);
+    TableReq &r = t->req[(size_t)q];
+    for (size_t b = 0; b < r.hbm.size(); b++) {
+        const int32_t id = r.hbm[b];
+        if (r.state[b] == KV_BLOCK_SYNCED) {
+            t->free_hbm.push(id);
+            released++;
+        } else {
+            if (r.slot[b] < 0) {
+                if (t->free_slot.empty()) return false;
+                r.slot[b] = t->free_slot.top();
+                t->free_slot.pop();
+            }
+            t->oi.push_back(id);
+            t->os.push_back(r.slot[b]);
+            t->held.push_back(id);
+        }
+        r.hbm[b] = -1;
+        r.state[b] = KV_BLOCK_HOST;
+    }
+    r.resident = false;
+    return true;
+}
+
+// A request comes back: every block gets the lowest free HBM id and joins the in
+// list; its slots stay its own.  False: the cache has no block left.
+static bool enter_hbm(kv_table *t, int32_t q)
+{
+    save_request(t, q);
+    TableReq &r = t->req[(size_t)q];
+    for (size_t b = 0; b < r.hbm.size(); b++) {
+        if (t->free_hbm.empty()) return false;
+        const int32_t id = t->free_hbm.top();
+        t->free_hbm.pop();
+        r.hbm[b] = id;
+        r.state[b] = KV_BLOCK_SYNCED;
+        t->ii.push_back(id);
+        t->is.push_back(r.slot[b]);
+    }
+    r.resident = true;
+    return true;
+}
+
+// A rotation is a transaction on the table: the requests leave and enter as if
+// the transfer had already been accepted, and whatever goes wrong on the way
+// (no slot left, no block left, the engine refusing the transfer) ends in
+// end_undo(false), which puts every request, both free sets and the counters
+// back.  So there is no counting of room beforehand: running out is found by
+// running out.
 static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int32_t *res, int32_t n_res,
                        int32_t eager_budget, int32_t *n_eager)
 {
     if (!t || list_bad(pre, n_pre) || list_bad(res, n_res) || eager_budget < 0) return KV_EINVAL;
-    // who is named, and is each one in the right place
-    int rc = KV_OK;
-    for (int32_t i = 0; i < n_pre && rc == KV_OK; i++) {
-        if (pre[i] < 0 || pre[i] >= t->max_req) { rc = KV_EINVAL; break; }
-        TableReq &r = t->req[(size_t)pre[i]];
-        if (!r.used || !r.resident || t->seen[(size_t)pre[i]]) rc = KV_EINVAL;
-        else t->seen[(size_t)pre[i]] = 1;
-    }
-    for (int32_t i = 0; i < n_res && rc == KV_OK; i++) {
-        if (res[i] < 0 || res[i] >= t->max_req) { rc = KV_EINVAL; break; }
-        TableReq &r = t->req[(size_t)res[i]];
-        if (!r.used || r.resident || t->seen[(size_t)res[i]]) rc = KV_EINVAL;
-        else t->seen[(size_t)res[i]] = 1;
-    }
-    for (int32_t i = 0; i < n_pre; i++)
-        if (pre[i] >= 0 && pre[i] < t->max_req) t->seen[(size_t)pre[i]] = 0;
-    for (int32_t i = 0; i < n_res; i++)
-        if (res[i] >= 0 && res[i] < t->max_req) t->seen[(size_t)res[i]] = 0;
-    if (rc != KV_OK) return rc;
-    // room, before anything changes
-    int64_t need_slots = 0, drop = 0, need_hbm = 0;
-    for (int32_t i = 0; i < n_pre; i++) {
-        const TableReq &r = t->req[(size_t)pre[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            if (r.state[b] == KV_BLOCK_SYNCED) drop++;
-            else if (r.slot[b] < 0) need_slots++;
-        }
-    }
-    for (int32_t i = 0; i < n_res; i++) need_hbm += (int64_t)t->req[(size_t)res[i]].hbm.size();
-    if (need_slots > (int64_t)t->free_slot.size()) return KV_ENOSPC;
-    if (need_hbm > (int64_t)t->free_hbm.size() + drop) return KV_ENOSPC;
-
-    // From here on the table is changed as if the transfer had been accepted;
-    // should the engine refuse it after all, end_undo() puts everything back.
+    if (!names_ok(t, pre, n_pre, res, n_res)) return KV_EINVAL;
     begin_undo(t);
     t->oi.clear(); t->os.clear(); t->ii.clear(); t->is.clear(); t->held.clear();
-    int64_t n_drop = 0;
-    for (int32_t i = 0; i < n_pre; i++) {
-        save_request(t, pre[i]);
-        TableReq &r = t->req[(size_t)pre[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            if (r.state[b] == KV_BLOCK_SYNCED) {
-                t->free_hbm.push(r.hbm[b]);  // no byte moves; reusable by this call's swap-ins
-                n_drop++;
-            } else {
-                if (r.slot[b] < 0) {
-                    r.slot[b] = t->free_slot.top();
-                    t->free_slot.pop();
-                }
-                t->oi.push_back(r.hbm[b]);
-                t->os.push_back(r.slot[b]);
-                t->held.push_back(r.hbm[b]);  // a source of this call: not a destination of it
-            }
-            r.hbm[b] = -1;
-            r.state[b] = KV_BLOCK_HOST;
-        }
-        r.resident = false;
-    }
-    for (int32_t i = 0; i < n_res; i++) {
-        save_request(t, res[i]);
-        TableReq &r = t->req[(size_t)res[i]];
-        for (size_t b = 0; b < r.hbm.size(); b++) {
-            const int32_t id = t->free_hbm.top();
-            t->free_hbm.pop();
-            r.hbm[b] = id;
-            r.state[b] = KV_BLOCK_SYNCED;
-            t->ii.push_back(id);
-            t->is.push_back(r.slot[b]);
-        }
-        r.resident = true;
+    int64_t released = 0;
+    bool fits = true;
+    for (int32_t i = 0; fits && i < n_pre; i++) fits = leave_hbm(t, pre[i], released);
+    for (int32_t i = 0; fits && i < n_res; i++) fits = enter_hbm(t, res[i]);
+    if (!fits) {
+        end_undo(t, false);
+        return KV_ENOSPC;
     }
     for (int32_t id : t->held) t->free_hbm.push(id);
-    t->cnt.copied_preempt += (int64_t)t->oi.size();
-    t->cnt.dropped_synced += n_drop;
-    t->cnt.swapped_in += (int64_t)t->ii.size();
-    // the eager step of the requests that stay, riding in the same transfer
     const size_t n_preempt_copies = t->oi.size();
+    t->cnt.copied_preempt += (int64_t)n_preempt_copies;
+    t->cnt.dropped_synced += released;
+    t->cnt.swapped_in += (int64_t)t->ii.size();
+    // the eager step of the requests that are resident now, riding in the same transfer
     std::vector<std::pair<int32_t, size_t>> picked;
     std::vector<int32_t> fresh;
     if (eager_budget > 0) {
@@ -347,11 +369,10 @@ static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int
         mark_synced(t, picked, n_preempt_copies, true);
         t->cnt.copied_eager += (int64_t)picked.size();
     }
-    // The table's own bookkeeping guarantees what admission checks, so a refusal
-    // here is a shape the path cannot serve or a HIP error: nothing was enqueued,
-    // and the table goes back to what it was.
-    rc = kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
-                   (int32_t)t->ii.size());
+    // The lists are conflict-free by construction, so a refusal here is a shape the
+    // path cannot serve or a HIP error; nothing was enqueued.
+    const int rc = kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
+                             (int32_t)t->ii.size());
     end_undo(t, rc == KV_OK);
     if (n_eager) *n_eager = rc == KV_OK ? (int32_t)picked.size() : 0;
     return rc;

@@ -141,3 +141,72 @@ def test_admission_and_the_size_limit():
     assert B.kv_rotate_static(st.cfg, host.ctypes.data, st.pinned.data_ptr(), 0, rot.out_ids, rot.out_slots,
                               rot.in_ids, rot.in_slots) == B.KV_EINVAL
     case.close()
+
+
+def test_llama3_8b_full_size_matches_kv_rotate():
+    """configs[1] in bench.py's shape: 16 GiB cache, 128 scattered blocks each way."""
+    shape = W.SHAPES["llama3_8b"]
+    rot = W.config_rotation("llama3_8b")
+    seed = W.value_seed("llama3_8b")
+    cfg = B.make_config(shape)
+    caches = [W.cache_image(shape, seed, device="cuda") for _ in range(2)]
+    assert torch.equal(caches[0].view(torch.int16), caches[1].view(torch.int16))
+    eng = B.Engine(cfg, caches[0].data_ptr())
+    pool_a = eng.host_pool_array()
+    pinned = torch.empty(B.kv_pool_bytes(cfg), dtype=torch.uint8).pin_memory()
+    pool_b = pinned.numpy()
+    staged = W.staged_blocks(shape, len(rot.in_slots), seed + 50, device="cuda").view(torch.int16).cpu().numpy()
+    for pool in (pool_a, pool_b):
+        pool[:] = 0x5A
+        pool.view(np.int16).reshape((shape.n_host_slots,) + shape.block_dims())[rot.in_slots] = staged
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for r in (rot, rot.inverse(), rot):
+        assert eng.kv_rotate(r.out_ids, r.out_slots, r.in_ids, r.in_slots) == 0
+        assert B.kv_rotate_static(cfg, caches[1].data_ptr(), pinned.data_ptr(), stream.cuda_stream,
+                                  r.out_ids, r.out_slots, r.in_ids, r.in_slots) == 0
+    assert eng.kv_wait() == 0
+    stream.synchronize()
+    assert torch.equal(caches[0].view(torch.int16), caches[1].view(torch.int16)), "cache differs from kv_rotate's"
+    assert np.array_equal(pool_a, pool_b), "pool differs from kv_rotate's"
+    # and the rotation really happened: the swapped-in blocks hold the staged bytes
+    got = caches[1].view(torch.int16)[:, :, torch.from_numpy(rot.in_ids).long().cuda()].cpu().numpy()
+    assert np.array_equal(got.transpose(2, 0, 1, 3, 4, 5), staged)
+    eng.kv_destroy()
+
+
+def test_replays_of_a_captured_call():
+    """The call for which the entry point exists: recorded into a HIP graph and
+    replayed.  Between replays the program changes what the blocks and slots hold,
+    with its own eager work and synchronisations, and every replay must move the
+    bytes that are there at that moment."""
+    case, rot = make_case("small8b", B.KV_HOST_BLOCK_FIRST, B.KV_PATH_AUTO)
+    shape, cfg = case.shape, case.cfg
+    dev = torch.from_numpy(case.ref_cache.view(np.int16).copy()).cuda()
+    pinned = torch.from_numpy(case.ref_pool.view(np.int16).copy()).pin_memory()
+    stream = torch.cuda.Stream()
+    args = (rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots)
+    # first call outside any capture: it looks up the scratch array's address on this device
+    assert B.kv_rotate_static(cfg, dev.data_ptr(), pinned.data_ptr(), stream.cuda_stream, *args) == 0
+    stream.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        rc = B.kv_rotate_static(cfg, dev.data_ptr(), pinned.data_ptr(), torch.cuda.current_stream().cuda_stream, *args)
+    assert rc == 0
+    dv = dev.view(shape.n_layers, 2, shape.n_hbm_blocks, shape.block_size, shape.n_kv_heads, shape.head_dim)
+    pv = pinned.view((shape.n_host_slots,) + shape.block_dims())
+    out_ids, in_ids = torch.from_numpy(rot.out_ids).long().cuda(), torch.from_numpy(rot.in_ids).long().cuda()
+    g = torch.Generator(device="cuda").manual_seed(5)
+    for k in range(4):
+        # new contents for the blocks that leave and for the slots that come in
+        fresh = torch.randint(-32768, 32767, dv[:, :, out_ids].shape, generator=g, dtype=torch.int16, device="cuda")
+        dv[:, :, out_ids] = fresh
+        incoming = torch.from_numpy(np.random.default_rng(k).integers(-32768, 32767, size=(len(rot.in_slots),) +
+                                    shape.block_dims(), dtype=np.int16))
+        pv[torch.from_numpy(rot.in_slots).long()] = incoming
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(pv[torch.from_numpy(rot.out_slots).long()], fresh.cpu().permute(2, 0, 1, 3, 4, 5)), f"replay {k}: out"
+        assert torch.equal(dv[:, :, in_ids].cpu().permute(2, 0, 1, 3, 4, 5), incoming), f"replay {k}: in"
+    case.close()
