@@ -8,7 +8,9 @@
 //     kernels, and above the DMA engines' duplex rate);
 //   - a single direction (the other list empty): zero-copy swap-out or swap-in;
 //   - pack / unpack between the scattered cache and a contiguous staging
-//     buffer in HBM (the "far" side is then device memory, slot = list index).
+//     buffer in HBM (the "far" side is then device memory, slot = list index)
+//     when the launch is capped to a few workgroups; uncapped, pack / unpack
+//     have a kernel of their own, kv_stage_kernel.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -326,7 +328,8 @@ __device__ __forceinline__ void run_drawn(const MoveParams &p, const int32_t *__
 // end within one tile of each other, and the rate no longer depends on how the
 // wave count divides the tile count.  The last wave to finish puts both
 // counters back to zero for the next launch on the stream.  HBM-bound launches
-// (pack / unpack) move a tile in ~2 ns chip-wide, too fast for one counter, and
+// (pack / unpack with a cap on their workgroups; uncapped they run as
+// kv_stage_kernel) move a tile in ~2 ns chip-wide, too fast for one counter, and
 // use the fixed share.
 template <typename V, int U, bool LINK>
 __global__ __launch_bounds__(kMaxThreads) void kv_move_kernel(const MoveParams p,

@@ -159,6 +159,20 @@ def test_workgroup_cap(max_wgs):
     case.close()
 
 
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("name,max_wgs,staging", [("small8b", 1, 0), ("small8b", 64, 2 << 20), ("ragged", 3, 0),
+                                                  ("tiny", 2, 0)])
+def test_staged_path_with_capped_workgroups(name, max_wgs, staging, layout):
+    """With a cap on its workgroups the DMA-staged path packs and unpacks with
+    persistent waves of the general move kernel instead of one wave per tile."""
+    case, rot = make_case(name, layout, B.KV_PATH_SDMA_STAGED, max_copy_wgs=max_wgs, staging_bytes=staging)
+    case.rotate(rot)
+    case.check()
+    case.rotate(rot.inverse())
+    case.check()
+    case.close()
+
+
 def test_unaligned_segments_use_narrow_vectors():
     """Segment sizes that are not multiples of 16 bytes (2-byte and 1-byte lanes)."""
     for sh in [W.KVShape(2, 1, 3, 1, n_hbm_blocks=11, n_host_slots=9, elem_bytes=2),   # 6 B
