@@ -82,7 +82,8 @@ typedef struct {
     int32_t n_host_slots;  /* block slots in the host pool */
     int32_t host_layout;   /* KV_HOST_* */
     int32_t path;          /* KV_PATH_* */
-    int32_t chunk_layers;  /* layers per pipeline chunk; 0 = engine picks */
+    int32_t chunk_layers;  /* layers per chunk: DMA-staged path, 0 = engine picks; kernel paths, 0 = one launch, c > 0 =
+                              c layers per launch with a completion mark each (kv_stream_wait_layer) */
     int32_t max_copy_wgs;  /* workgroups (of wg_lanes lanes; of 256 if wg_lanes is 0) a copy kernel may occupy; 0 = engine picks */
     int32_t vecs_per_lane; /* 16-byte vectors each lane keeps in flight per direction in the link kernels: 0 = engine picks, else 1, 2, 4 or 8 */
     int32_t wg_lanes;      /* lanes per workgroup of the link kernels (workgroups only pack waves; a wave is the unit of work):
@@ -206,6 +207,29 @@ int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, voi
 /* Blocks until everything enqueued so far is done; the host pool is then
  * coherent for CPU reads.  Closes the interval kv_last_stats() reports. */
 int kv_wait(kv_engine *engine);
+
+/*
+ * Layer by layer (north_star: "per-layer chunking so that the transfers
+ * overlap"; the paper overlaps the rotation for iteration t+1 with the execution
+ * of iteration t, Section 4.3.2).  With cfg.chunk_layers = c > 0 the kernel paths
+ * (KV_PATH_FUSED, KV_PATH_ZEROCOPY, and KV_PATH_AUTO, which picks one of them)
+ * move a call's blocks c layers at a time, lowest layers first, one launch per
+ * chunk, and mark the end of every chunk.  A consumer can then start on layer l
+ * while the layers behind it still move:
+ *   kv_stream_wait_layer: work enqueued on `stream` (a hipStream_t of the
+ *     caller's, e.g. the model's compute stream) after this call starts only
+ *     once layer `layer` of the most recent transfer call is in place: K and V
+ *     of that layer of every block the call names, in both directions.
+ *   kv_wait_layer: the same for the host; it blocks until then.  The stats
+ *     interval stays open (only kv_wait closes it).
+ * After a call that did not run layer by layer (chunk_layers 0, or one of the
+ * DMA paths) both wait for the whole call.  KV_EINVAL for a layer outside
+ * [0, n_layers).  The chunks cost a launch each (a few microseconds between
+ * launches and a ramp per launch): meant for large rotations, where a chunk is
+ * tens of MiB or more.
+ */
+int kv_stream_wait_layer(kv_engine *engine, void *stream, int32_t layer);
+int kv_wait_layer(kv_engine *engine, int32_t layer);
 
 /* Host address and size of the pool (for filling / checking it from the CPU). */
 int kv_host_pool(kv_engine *engine, void **ptr, uint64_t *bytes);

@@ -373,6 +373,31 @@ void launch_stage(int vec, hipStream_t s, const dkv::StageParams &p, const int32
 }
 
 // ---- FUSED / ZEROCOPY -----------------------------------------------------
+// One link-bound launch, or, with cfg.chunk_layers set, one launch per chunk of
+// that many layers, lowest layers first, each followed by an event in `ev`, so
+// that whoever consumes the blocks (the model's layer l, a writer of the pool)
+// can start on a layer while the later ones still move.  A chunk is the same
+// kernel over planes [p0, p1) of every block of the call.
+int launch_link(kv_engine *e, const LinkShape &sh, hipStream_t s, const MoveParams &whole, const MoveIds &ids,
+                std::vector<hipEvent_t> *ev)
+{
+    const uint32_t per_chunk = ev ? 2u * (uint32_t)e->cfg.chunk_layers : whole.n_planes;
+    uint32_t c = 0;
+    for (uint32_t p0 = 0; p0 < whole.n_planes; p0 += per_chunk, c++) {
+        MoveParams q = whole;
+        q.plane0 = p0;
+        q.n_planes = std::min(per_chunk, whole.n_planes - p0);
+        q.out.tiles = q.out.n * q.n_planes * q.tiles_per_seg;  // fits: the whole call's count was checked
+        q.in.tiles = q.in.n * q.n_planes * q.tiles_per_seg;
+        q.mix_q = whole.mix_q && q.out.tiles ? (((uint64_t)q.out.tiles << 32) + q.in.tiles - 1) / q.in.tiles : 0;
+        launch_move(sh.u, e->vec, sh.wgs, sh.lanes, s, q, ids, true);
+        HIPTRY(e, hipGetLastError());
+        e->acc.n_launches += 1;
+        if (ev) HIPTRY(e, hipEventRecord((*ev)[c], s));
+    }
+    return KV_OK;
+}
+
 int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
 {
     int32_t *dh = e->desc_host + (size_t)k * e->desc_cap;
@@ -422,7 +447,9 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         // 56.7 against 55.8 GB/s, and a co-runner keeps 5.9 instead of 3.0 TB/s),
         // right behind the paired part on the same stream.
         constexpr uint64_t kSplitBytes = 64ull << 20;
-        const int32_t n_rest = no > ni && (uint64_t)(no - ni) * e->block_bytes >= kSplitBytes ? no - ni : 0;
+        const bool layered = e->cfg.chunk_layers > 0;  // layer by layer: the whole out list stays in the one kernel
+        const int32_t n_rest =
+            !layered && no > ni && (uint64_t)(no - ni) * e->block_bytes >= kSplitBytes ? no - ni : 0;
         const int32_t no_paired = no - n_rest;
         const LinkShape sh_rest = link_shape(e, kOutOnly);
         MoveParams p = params(sh.u, e->claim), p_rest = params(sh_rest.u, e->claim);
@@ -447,9 +474,12 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
                 e->b_i0 = e->ev_i0;
             }
         }
-        launch_move(sh.u, e->vec, sh.wgs, sh.lanes, e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni}, true);
-        HIPTRY(e, hipGetLastError());
-        e->acc.n_launches += 1;
+        if (launch_link(e, sh, e->s_out, p, MoveIds{d_o, d_o + no, d_i, d_i + ni},
+                        layered ? &e->layer_ev_out : nullptr) != KV_OK)
+            return KV_EHIP;
+        e->layer_chunk = layered ? e->cfg.chunk_layers : 0;
+        e->layer_on_out = layered;
+        e->layer_on_in = false;
         if (n_rest > 0) {
             launch_move(sh_rest.u, e->vec, sh_rest.wgs, sh_rest.lanes, e->s_out, p_rest,
                         MoveIds{d_o + no_paired, d_o + no + no_paired, nullptr, nullptr}, true);
@@ -497,21 +527,23 @@ int run_zero_copy(kv_engine *e, int path, int k, int32_t no, int32_t ni)
         HIPTRY(e, hipStreamWaitEvent(e->s_in, e->ev_join_in, 0));
         e->out_dirty = false;
     }
+    const bool layered = e->cfg.chunk_layers > 0;
+    e->layer_chunk = layered ? e->cfg.chunk_layers : 0;
+    e->layer_on_out = layered && no > 0;
+    e->layer_on_in = layered && ni > 0;
     if (no > 0) {
         if (upload_ids(true, false, e->s_out) != KV_OK) return KV_EHIP;
         if (mark_start(e, true, e->s_out) != KV_OK) return KV_EHIP;
-        launch_move(sh_out.u, e->vec, sh_out.wgs, sh_out.lanes, e->s_out, p_out, ids_out, true);
-        HIPTRY(e, hipGetLastError());
+        if (launch_link(e, sh_out, e->s_out, p_out, ids_out, layered ? &e->layer_ev_out : nullptr) != KV_OK)
+            return KV_EHIP;
         if (mark_end(e, true, k, e->s_out) != KV_OK) return KV_EHIP;
-        e->acc.n_launches += 1;
     }
     if (ni > 0) {
         if (upload_ids(false, true, e->s_in) != KV_OK) return KV_EHIP;
         if (mark_start(e, false, e->s_in) != KV_OK) return KV_EHIP;
-        launch_move(sh_in.u, e->vec, sh_in.wgs, sh_in.lanes, e->s_in, p_in, ids_in, true);
-        HIPTRY(e, hipGetLastError());
+        if (launch_link(e, sh_in, e->s_in, p_in, ids_in, layered ? &e->layer_ev_in : nullptr) != KV_OK)
+            return KV_EHIP;
         if (mark_end(e, false, k, e->s_in) != KV_OK) return KV_EHIP;
-        e->acc.n_launches += 1;
     }
     return KV_OK;
 }
@@ -856,6 +888,7 @@ int transfer(kv_engine *e, const int32_t *oi, const int32_t *os, int32_t no, con
         if (rc != KV_OK) return rc;
     }
     open_batch(e);
+    e->layer_chunk = 0;  // the kernel paths set it again when they run layer by layer
     if (path == KV_PATH_NAIVE) {
         rc = run_naive(e, oi, os, no, ii, is, ni);
     } else if (path == KV_PATH_DMA_BLOCKS) {
@@ -895,6 +928,8 @@ void free_engine(kv_engine *e)
     auto ev = [](hipEvent_t &x) { if (x) { (void)hipEventDestroy(x); x = nullptr; } };
     for (int k = 0; k < kRing; k++) { ev(e->ring_out[k]); ev(e->ring_in[k]); }
     ev(e->ev_o0); ev(e->ev_o1); ev(e->ev_i0); ev(e->ev_i1); ev(e->ev_join); ev(e->ev_join_in);
+    for (hipEvent_t &x : e->layer_ev_out) ev(x);
+    for (hipEvent_t &x : e->layer_ev_in) ev(x);
     if (e->stage_out) (void)hipFree(e->stage_out);
     if (e->stage_in) (void)hipFree(e->stage_in);
     if (e->s_read) (void)hipStreamDestroy(e->s_read);
@@ -1154,6 +1189,13 @@ int kv_create(kv_engine **out, const kv_config *cfg, void *hbm_cache, void *host
     for (hipEvent_t *x : {&e->ev_o0, &e->ev_o1, &e->ev_i0, &e->ev_i1}) ok = ok && hipEventCreate(x) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&e->ev_join, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&e->ev_join_in, hipEventDisableTiming) == hipSuccess;
+    if (cfg->chunk_layers > 0) {
+        e->layer_n_chunks = (cfg->n_layers + cfg->chunk_layers - 1) / cfg->chunk_layers;
+        e->layer_ev_out.assign((size_t)e->layer_n_chunks, nullptr);
+        e->layer_ev_in.assign((size_t)e->layer_n_chunks, nullptr);
+        for (hipEvent_t &x : e->layer_ev_out) ok = ok && hipEventCreateWithFlags(&x, hipEventDisableTiming) == hipSuccess;
+        for (hipEvent_t &x : e->layer_ev_in) ok = ok && hipEventCreateWithFlags(&x, hipEventDisableTiming) == hipSuccess;
+    }
     if (!ok) return fail(KV_EHIP);
     e->marks.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
     e->hazards.reset((size_t)cfg->n_hbm_blocks, (size_t)cfg->n_host_slots);
@@ -1220,6 +1262,44 @@ int kv_wait(kv_engine *e)
         e->last = e->acc;
         e->batch_open = false;
     }
+    return KV_OK;
+}
+
+// The events behind which `layer` of the most recent transfer call is complete:
+// its chunk's events if that call ran layer by layer, else the call's end events.
+static int layer_events(kv_engine *e, int32_t layer, hipEvent_t (&out)[2])
+{
+    out[0] = out[1] = nullptr;
+    if (!e || layer < 0 || layer >= e->cfg.n_layers) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    if (e->layer_chunk > 0) {
+        const size_t c = (size_t)(layer / e->layer_chunk);
+        if (e->layer_on_out) out[0] = e->layer_ev_out[c];
+        if (e->layer_on_in) out[1] = e->layer_ev_in[c];
+    } else {
+        if (e->out_pending) out[0] = e->b_o1;
+        if (e->in_pending) out[1] = e->b_i1;
+    }
+    return KV_OK;
+}
+
+int kv_stream_wait_layer(kv_engine *e, void *stream, int32_t layer)
+{
+    hipEvent_t evs[2];
+    const int rc = layer_events(e, layer, evs);
+    if (rc != KV_OK) return rc;
+    for (hipEvent_t x : evs)
+        if (x) HIPTRY(e, hipStreamWaitEvent((hipStream_t)stream, x, 0));
+    return KV_OK;
+}
+
+int kv_wait_layer(kv_engine *e, int32_t layer)
+{
+    hipEvent_t evs[2];
+    const int rc = layer_events(e, layer, evs);
+    if (rc != KV_OK) return rc;
+    for (hipEvent_t x : evs)
+        if (x) HIPTRY(e, hipEventSynchronize(x));
     return KV_OK;
 }
 

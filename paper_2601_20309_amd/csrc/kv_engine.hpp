@@ -123,6 +123,15 @@ struct kv_engine {
     kv_stats acc{}, last{};
     int sticky = KV_OK;
 
+    // Layer-wise completion of the kernel paths (cfg.chunk_layers > 0): the last
+    // transfer call ran as layer_n_chunks launches of layer_chunk layers each and
+    // recorded layer_ev_*[c] behind chunk c.  layer_on_out / layer_on_in say which
+    // of the two event lists that call recorded (one launch for both directions
+    // records on stream_out only).  layer_chunk == 0: the last call was not chunked.
+    std::vector<hipEvent_t> layer_ev_out, layer_ev_in;
+    int32_t layer_chunk = 0, layer_n_chunks = 0;
+    bool layer_on_out = false, layer_on_in = false;
+
     // staging for SDMA_STAGED: one buffer per direction, chunk_cap bytes each.
     // A direction's pack / copy / unpack all run in order on that direction's
     // stream, so a buffer is never reused before its last reader is done.

@@ -10,6 +10,7 @@
   python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
   python -m paper_2601_20309_amd.experiments sizes         # rotation rate against rotation size
   python -m paper_2601_20309_amd.experiments ratio         # rates against the mix of the two directions
+  python -m paper_2601_20309_amd.experiments layers        # kernel paths layer by layer: cost of the chunks, when layer 0 is ready
   python -m paper_2601_20309_amd.experiments chunks        # DMA-staged path against chunk size: what serial chunks cost
   python -m paper_2601_20309_amd.experiments splitcalls    # configs[2] in one call, in 32 waited calls, in 32 un-waited calls
   python -m paper_2601_20309_amd.experiments packalone     # pack and unpack kernels with nothing beside them (profiling target)
@@ -351,6 +352,46 @@ def chunks(name="long70b"):
     a = my - b * mx
     print(f"\nfit: step ms = {a:.1f} + {b * 1e3:.1f} us x chunks per direction; with one chunk per layer "
           f"(80 chunks) the serial hand-overs cost {80 * b:.1f} ms = {100 * 80 * b / (a + 80 * b):.1f} % of the step")
+
+
+def layers(name="long70b"):
+    """The default path layer by layer (cfg.chunk_layers > 0): one launch per chunk
+    of layers with a completion mark each, so that a consumer can start on layer l
+    while later layers move.  For configs[3] (20 + 20 GiB, 80 layers): what the
+    chunks cost the whole rotation, and when the first and the middle layer are
+    in place (host clock from the call, kv_wait_layer)."""
+    shape = W.SHAPES[name]
+    cache = _cache(shape)
+    rot = W.config_rotation(name)
+    print(f"\n{name}: {len(rot.out_ids)} blocks out while {len(rot.in_ids)} come in, "
+          f"{len(rot.out_ids) * B.kv_block_bytes(B.make_config(shape)) / 2**30:.0f} GiB each way, {shape.n_layers} layers\n")
+    print("| layers per launch | launches | MiB per launch and direction | whole rotation ms | GB/s per direction | "
+          "layer 0 in place after ms | middle layer in place after ms |")
+    print("|---|---|---|---|---|---|---|")
+    for chunk in (0, 16, 8, 4, 2, 1):
+        eng = B.Engine(B.make_config(shape, chunk_layers=chunk), cache.data_ptr())
+        blk = B.kv_block_bytes(eng.cfg)
+        calls = _rot_calls(eng, rot)
+        t_all, t_first, t_mid = [], [], []
+        for i in range(6):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            assert calls[i & 1]() == 0
+            assert eng.kv_wait_layer(0) == 0
+            t1 = time.perf_counter()
+            assert eng.kv_wait_layer(shape.n_layers // 2) == 0
+            t2 = time.perf_counter()
+            assert eng.kv_wait() == 0
+            t3 = time.perf_counter()
+            if i >= 2:
+                t_first.append((t1 - t0) * 1e3); t_mid.append((t2 - t0) * 1e3); t_all.append((t3 - t0) * 1e3)
+        ms = statistics.median(t_all)
+        n_launch = eng.kv_last_stats()["n_launches"]
+        per = len(rot.out_ids) * blk / n_launch / 2**20
+        print(f"| {chunk if chunk else 'all (one launch)'} | {n_launch} | {per:.0f} | {ms:.1f} | "
+              f"{len(rot.out_ids) * blk / ms / 1e6:.2f} | {statistics.median(t_first):.1f} | {statistics.median(t_mid):.1f} |",
+              flush=True)
+        eng.kv_destroy()
 
 
 def splitcalls():
@@ -914,5 +955,5 @@ if __name__ == "__main__":
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
      "linksweep": linksweep, "serve": serve,
-     "sizes": sizes, "ratio": ratio, "chunks": chunks, "splitcalls": splitcalls, "packalone": packalone,
+     "sizes": sizes, "ratio": ratio, "chunks": chunks, "layers": layers, "splitcalls": splitcalls, "packalone": packalone,
      "packshapes": packshapes}[what]()

@@ -61,16 +61,18 @@ def test_batch_rotation_full_size():
 
 @pytest.mark.parametrize("path,layout,chunk_layers", [
     (B.KV_PATH_AUTO, B.KV_HOST_BLOCK_FIRST, 0),
+    (B.KV_PATH_AUTO, B.KV_HOST_LAYER_FIRST, 1),
     (B.KV_PATH_SDMA_STAGED, B.KV_HOST_LAYER_FIRST, 1),
 ])
 def test_long70b_rotation_full_size(path, layout, chunk_layers, say):
     """configs[3]: 80 layers, 64 KiB segments, 10 MiB blocks, a 45 GiB cache and a
     40 GiB pool; two 32768-token requests leave while two come back (20 GiB each
     way, the transfer size of the paper's Section 5.4 / Table 2 per direction), in
-    one launch on the default path and chunked per layer on the DMA path."""
+    one launch on the default path, layer by layer on the default path (80 launches,
+    each with its completion mark), and chunked per layer on the DMA path."""
     shape = W.SHAPES["long70b"]
     assert shape.n_hbm_blocks == 4608 and shape.n_host_slots == 4096
-    rot = W.config_rotation("long70b", contiguous_slots=chunk_layers == 1)
+    rot = W.config_rotation("long70b", contiguous_slots=path == B.KV_PATH_SDMA_STAGED)
     assert len(rot.out_ids) == len(rot.in_ids) == 2048
     case = BigCase("long70b", layout=layout, path=path, chunk_layers=chunk_layers, say=say)
     blk = B.kv_block_bytes(case.cfg)
@@ -80,11 +82,12 @@ def test_long70b_rotation_full_size(path, layout, chunk_layers, say):
     case.check()
     st = case.eng.kv_last_stats()
     assert st["bytes_out"] == st["bytes_in"] == 20 << 30
-    if chunk_layers == 1:
+    if path == B.KV_PATH_SDMA_STAGED:
         # 80 layer chunks per direction, each one pack / unpack kernel + 2 plane copies
         assert st["path_used"] == B.KV_PATH_SDMA_STAGED and st["n_launches"] == 2 * 80 * 3
     else:
-        assert st["path_used"] == B.KV_PATH_FUSED and st["n_launches"] == 1
+        assert st["path_used"] == B.KV_PATH_FUSED and st["n_launches"] == (80 if chunk_layers == 1 else 1)
+        assert case.eng.kv_wait_layer(79) == 0
     case.close()
 
 
