@@ -222,8 +222,10 @@ int kv_wait(kv_engine *engine);
  *     of that layer of every block the call names, in both directions.
  *   kv_wait_layer: the same for the host; it blocks until then.  The stats
  *     interval stays open (only kv_wait closes it).
- * After a call that did not run layer by layer (chunk_layers 0, or one of the
- * DMA paths) both wait for the whole call.  KV_EINVAL for a layer outside
+ * KV_PATH_SDMA_STAGED marks its chunks the same way when a chunk is chunk_layers
+ * layers of the whole list (the staging buffer holds that much).  After a call
+ * that did not run layer by layer (chunk_layers 0, a list cut to fit the staging
+ * buffer, the per-copy DMA paths) both wait for the whole call.  KV_EINVAL for a layer outside
  * [0, n_layers).  The chunks cost a launch each (a few microseconds between
  * launches and a ramp per launch): meant for large rotations, where a chunk is
  * tens of MiB or more.

@@ -800,6 +800,18 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
     co.done = no == 0;
     ci.done = ni == 0;
     int32_t n_ops = 0;
+    // Layer by layer for a consumer (kv_stream_wait_layer): possible when a chunk is
+    // chunk_layers layers of the whole list, i.e. the staging buffer did not force
+    // the list or the chunk to be cut; then chunk c is layers [c * chunk_layers, ...).
+    const uint32_t want_planes = 2u * (uint32_t)e->cfg.chunk_layers;
+    const bool lay_out = want_planes && no > 0 && po.blocks_per_chunk >= (uint32_t)no &&
+                         po.planes_per_chunk == std::min(want_planes, e->n_planes);
+    const bool lay_in = want_planes && ni > 0 && pi.blocks_per_chunk >= (uint32_t)ni &&
+                        pi.planes_per_chunk == std::min(want_planes, e->n_planes);
+    const bool layered = (lay_out || no == 0) && (lay_in || ni == 0);
+    e->layer_chunk = layered ? e->cfg.chunk_layers : 0;
+    e->layer_on_out = layered && no > 0;
+    e->layer_on_in = layered && ni > 0;
     while (!co.done || !ci.done) {
         if (!co.done) {
             const uint32_t j1 = std::min<uint32_t>(co.j0 + po.blocks_per_chunk, (uint32_t)no);
@@ -818,6 +830,7 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
             HIPTRY(e, hipGetLastError());
             if (chunk_copies(e, true, e->stage_out, h_out + no, co.j0, j1, co.p0, p1, e->s_out, n_ops) != KV_OK)
                 return KV_EHIP;
+            if (layered) HIPTRY(e, hipEventRecord(e->layer_ev_out[co.p0 / po.planes_per_chunk], e->s_out));
             n_ops++;
             co.p0 = p1;
             if (co.p0 >= e->n_planes) { co.p0 = 0; co.j0 = j1; }
@@ -840,6 +853,7 @@ int run_staged(kv_engine *e, int k, const int32_t *oi, const int32_t *os, int32_
                 launch_stage<true>(e->vec, e->s_in, q, d_in + ci.j0);
             }
             HIPTRY(e, hipGetLastError());
+            if (layered) HIPTRY(e, hipEventRecord(e->layer_ev_in[ci.p0 / pi.planes_per_chunk], e->s_in));
             n_ops++;
             ci.p0 = p1;
             if (ci.p0 >= e->n_planes) { ci.p0 = 0; ci.j0 = j1; }

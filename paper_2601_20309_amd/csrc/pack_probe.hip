@@ -202,14 +202,14 @@ int main()
     printf("|---|---|---|---|---|---|---|\n");
     // check: 1 = the staging must equal the reference gather; 0 = nothing to compare (copy / unpack)
     auto run = [&](const char *name, const char *grid, int check, auto launch) {
-        const char *verdict = "-";
+        const char *same = "-";
         if (check) {
             CK(hipMemsetAsync(stage, 0, chunk_b, s));
             CK(hipMemsetAsync(counter, 0, 256, s));
             launch();
             CK(hipStreamSynchronize(s));
             CK(hipMemcpy(got.data(), stage, chunk_b, hipMemcpyDeviceToHost));
-            verdict = memcmp(got.data(), want.data(), chunk_b) == 0 ? "equal" : "DIFFERS";
+            same = memcmp(got.data(), want.data(), chunk_b) == 0 ? "equal" : "DIFFERS";
         }
         std::vector<float> us;
         for (uint32_t r = 0; r < 34; r++) {
@@ -228,7 +228,7 @@ int main()
         c.stage = stage;
         std::sort(us.begin(), us.end());
         const double med = us[us.size() / 2], tbs = 2.0 * chunk_b / med / 1e6;
-        printf("| %s | %s | %s | %.1f | %.1f | %.2f | %.0f %% |\n", name, grid, verdict, med, us[0], tbs, tbs / 8 * 100);
+        printf("| %s | %s | %s | %.1f | %.1f | %.2f | %.0f %% |\n", name, grid, same, med, us[0], tbs, tbs / 8 * 100);
         fflush(stdout);
     };
 #define FIXED(U, L, S, UNP, G, T) \

@@ -117,11 +117,32 @@ def test_unchunked_calls_wait_for_the_whole_call():
     assert np.array_equal(snap.cpu().numpy().view(np.uint16), case.ref_cache)
     assert case.eng.kv_wait_layer(3) == 0
     case.check()
-    # the DMA-staged path chunks for its staging buffer, not layer by layer for a consumer
-    case2, rot2 = make_case("small8b", B.KV_HOST_LAYER_FIRST, B.KV_PATH_SDMA_STAGED, chunk_layers=1)
-    case2.rotate(rot2)
-    assert case2.eng.kv_wait_layer(0) == 0
-    assert np.array_equal(case2.dev_cache.cpu().numpy().view(np.uint16), case2.ref_cache)
-    case2.check()
     case.close()
-    case2.close()
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("staging", [0, 1 << 20])
+def test_dma_staged_path_marks_its_layer_chunks(layout, staging):
+    """One chunk per layer of the whole list: each chunk gets its mark.  With a staging
+    buffer too small for a layer of the whole list (1 MiB) the list is cut and the waits
+    fall back to the whole call; either way, what is waited for is in place."""
+    case, rot = make_case("small8b", layout, B.KV_PATH_SDMA_STAGED, chunk_layers=1, staging_bytes=staging)
+    sh = case.shape
+    side = torch.cuda.Stream()
+    dv = case.dev_cache.view(sh.n_layers, 2, sh.n_hbm_blocks, sh.block_size, sh.n_kv_heads, sh.head_dim)
+    in_ids = torch.from_numpy(rot.in_ids).long().cuda()
+    snaps = [torch.empty((1, 2, len(rot.in_ids)) + dv.shape[3:], dtype=torch.int16, device="cuda")
+             for _ in range(sh.n_layers)]
+    torch.cuda.synchronize()
+    case.rotate(rot)
+    for l in range(sh.n_layers):
+        assert case.eng.kv_stream_wait_layer(side.cuda_stream, l) == 0
+        with torch.cuda.stream(side):
+            torch.index_select(dv[l:l + 1], 2, in_ids, out=snaps[l])
+    assert case.eng.kv_wait_layer(sh.n_layers - 1) == 0
+    side.synchronize()
+    want = V.hbm_view(sh, case.ref_cache)[:, :, rot.in_ids]
+    for l in range(sh.n_layers):
+        assert np.array_equal(snaps[l].cpu().numpy().view(np.uint16)[0], want[l]), f"layer {l}"
+    case.check()
+    case.close()
