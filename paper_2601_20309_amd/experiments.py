@@ -10,6 +10,7 @@
   python -m paper_2601_20309_amd.experiments serve         # LVF + block table + engine in a cross-iteration pipeline
   python -m paper_2601_20309_amd.experiments sizes         # rotation rate against rotation size
   python -m paper_2601_20309_amd.experiments ratio         # rates against the mix of the two directions
+  python -m paper_2601_20309_amd.experiments poolkinds     # does the kind of pinned memory the pool is made of matter?
   python -m paper_2601_20309_amd.experiments layers        # kernel paths layer by layer: cost of the chunks, when layer 0 is ready
   python -m paper_2601_20309_amd.experiments chunks        # DMA-staged path against chunk size: what serial chunks cost
   python -m paper_2601_20309_amd.experiments splitcalls    # configs[2] in one call, in 32 waited calls, in 32 un-waited calls
@@ -392,6 +393,52 @@ def layers(name="long70b"):
               f"{len(rot.out_ids) * blk / ms / 1e6:.2f} | {statistics.median(t_first):.1f} | {statistics.median(t_mid):.1f} |",
               flush=True)
         eng.kv_destroy()
+
+
+def poolkinds():
+    """The pool as different kinds of pinned host memory (hipHostMalloc flags),
+    handed to the engine as a caller-owned pool: the configs[1] rotation, a
+    2 + 2 GiB rotation and each direction alone."""
+    import ctypes as C
+    hip = C.CDLL("libamdhip64.so")      # the runtime torch has already loaded
+    hip.hipHostMalloc.argtypes = [C.POINTER(C.c_void_p), C.c_size_t, C.c_uint]
+    hip.hipHostFree.argtypes = [C.c_void_p]
+    shape = W.SHAPES["llama3_8b"]
+    cache = _cache(shape)
+    rot, big = W.config_rotation("llama3_8b"), W.simple_rotation(shape, 1024, 1024, seed=3)
+    kinds = [("default (what the engine allocates)", 0), ("portable + mapped", 0x3), ("write-combined", 0x4),
+             ("coherent", 0x40000000), ("non-coherent", 0x80000000), ("non-coherent + write-combined", 0x80000004),
+             ("NUMA-user", 0x20000000)]
+    print("\n| hipHostMalloc flags | 128 + 128 blocks GB/s (sum) | 1024 + 1024 blocks GB/s (sum) | swap-out alone GB/s | swap-in alone GB/s |")
+    print("|---|---|---|---|---|")
+    for name, flags in kinds:
+        cfg = B.make_config(shape)
+        blk = B.kv_block_bytes(cfg)
+        ptr = C.c_void_p()
+        if hip.hipHostMalloc(C.byref(ptr), B.kv_pool_bytes(cfg), flags) != 0:
+            print(f"| {name} | allocation refused | | | |", flush=True)
+            continue
+        eng = B.Engine(cfg, cache.data_ptr(), ptr.value)
+        row = []
+        for r in (rot, big):
+            calls = _rot_calls(eng, r)
+
+            def fn(i):
+                assert calls[i & 1]() == 0 and eng.kv_wait() == 0
+            ms, _, _ = _time_calls(eng, fn, 20, warm=4)
+            row.append((len(r.out_ids) + len(r.in_ids)) * blk / ms / 1e6)
+
+        def out_only(i):
+            assert eng.kv_swap_out(big.out_ids, big.out_slots) == 0 and eng.kv_wait() == 0
+
+        def in_only(i):
+            assert eng.kv_swap_in(big.out_slots, big.out_ids) == 0 and eng.kv_wait() == 0
+        for fn in (out_only, in_only):
+            ms, _, _ = _time_calls(eng, fn, 10, warm=2)
+            row.append(len(big.out_ids) * blk / ms / 1e6)
+        print(f"| {name} | " + " | ".join(f"{v:.2f}" for v in row) + " |", flush=True)
+        eng.kv_destroy()
+        hip.hipHostFree(ptr)
 
 
 def splitcalls():
@@ -955,5 +1002,5 @@ if __name__ == "__main__":
     {"ladder": ladder, "configs": configs, "interference": interference, "reader": reader,
      "eager": eager, "layouts": layouts,
      "linksweep": linksweep, "serve": serve,
-     "sizes": sizes, "ratio": ratio, "chunks": chunks, "layers": layers, "splitcalls": splitcalls, "packalone": packalone,
+     "sizes": sizes, "ratio": ratio, "chunks": chunks, "layers": layers, "poolkinds": poolkinds, "splitcalls": splitcalls, "packalone": packalone,
      "packshapes": packshapes}[what]()
