@@ -49,7 +49,10 @@ class FreeIds {
         }
         return -1;
     }
-    void pop() { flip(top(), false); }
+    void pop()
+    {
+        if (count_ > 0) flip(top(), false);
+    }
     void open_journal()
     {
         journal_.clear();

@@ -21,5 +21,6 @@ def test_example_rotates_and_verifies_on_the_gpu():
     run = subprocess.run([exe, "128"], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-2000:]
     assert "rotation verified on the CPU: 128 blocks out, 128 in" in run.stdout
+    assert "kv_rotate_static verified on the CPU" in run.stdout
     m = re.search(r"duplex rotation: ([0-9.]+) ms, ([0-9.]+) GB/s", run.stdout)
     assert m and float(m.group(2)) > 60.0, run.stdout

@@ -239,14 +239,15 @@ def test_llama_shape_preemption_moves_one_block_per_request():
     eng.kv_destroy()
 
 
-@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY])
-def test_back_to_back_table_calls_without_waiting(path):
+@pytest.mark.parametrize("path,chunk_layers", [(B.KV_PATH_AUTO, 0), (B.KV_PATH_ZEROCOPY, 0), (B.KV_PATH_AUTO, 3)])
+def test_back_to_back_table_calls_without_waiting(path, chunk_layers):
     """Eager copies, preemptions and resumptions enqueued back to back: blocks that
     one call vacates are refilled by the next while the first may still be running,
     so this only passes if the table orders its transfers across the two streams
-    (on the two-kernel path every rotation puts one kernel on each stream)."""
+    (on the two-kernel path every rotation puts one kernel on each stream; with
+    chunk_layers every transfer is several launches, layer by layer)."""
     sh = W.KVShape(8, 8, 128, 16, n_hbm_blocks=96, n_host_slots=256)     # 512 KiB blocks
-    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=6, seed=7, path=path)
+    s = BothSides(sh, B.KV_HOST_BLOCK_FIRST, max_req=6, seed=7, path=path, chunk_layers=chunk_layers)
     for r in range(4):
         s.append(r, 16 * 22 + 5)              # 22 full blocks + a tail; 4 x 23 = 92 of 96 blocks
     s.check(6)
