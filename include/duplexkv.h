@@ -228,7 +228,10 @@ int kv_wait(kv_engine *engine);
  * buffer, the per-copy DMA paths) both wait for the whole call.  KV_EINVAL for a layer outside
  * [0, n_layers).  The chunks cost a launch each (a few microseconds between
  * launches and a ramp per launch): meant for large rotations, where a chunk is
- * tens of MiB or more.
+ * tens of MiB or more.  A mark is never seen early; it can be seen late: the
+ * process's streams share a few hardware queues, and a consumer stream that
+ * shares one with the engine's stream runs behind the launches already queued
+ * there.
  */
 int kv_stream_wait_layer(kv_engine *engine, void *stream, int32_t layer);
 int kv_wait_layer(kv_engine *engine, int32_t layer);
