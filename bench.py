@@ -240,7 +240,10 @@ def main():
         log("whole cache verified after the timed loop")
 
     path_name = B.PATH_NAMES[st["path_used"]]
-    traffic, traffic_src = measured_traffic(args.workload, path_name, "kv_move_kernel")
+    # the kernel of the step: the move kernel, or, on the DMA-staged path, the pack / unpack kernel
+    # (its bench-traffic line is per launch of that kernel, one chunk)
+    traffic, traffic_src = measured_traffic(args.workload, path_name,
+                                            "kv_stage_kernel" if path_name == "sdma_staged" else "kv_move_kernel")
     res = {
         "metric": "duplex KV rotation GB/s (out+in) and % of measured host-link peak",
         "value": round(gbps_out + gbps_in, 2), "unit": "GB/s", "n_gpus": 1, "steps": steps,
