@@ -273,7 +273,9 @@ def main():
                                                   (link["d2h"] + link["h2d"]), 4),
             "kernel_ms": round(kern_ms, 4),
             "traffic": traffic, "profile": traffic_src,
-            "traffic_algorithmic": 2 * (bytes_out + bytes_in),
+            # per launch: the move kernel reads and writes both directions' bytes once; a pack or
+            # unpack launch reads and writes one direction's
+            "traffic_algorithmic": 2 * bytes_out if path_name == "sdma_staged" else 2 * (bytes_out + bytes_in),
             "hbm_frac": round((bytes_out + bytes_in) / (kern_ms * 1e6) / HBM_PEAK_GBPS, 5),
         },
     }
