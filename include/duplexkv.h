@@ -192,7 +192,8 @@ int kv_rotate(kv_engine *engine,
  * (hipStreamSynchronize, or an event of the caller's).  Every call on a GPU
  * shares that GPU's array, so calls on one GPU must be ordered one after the
  * other (the same stream, or streams the caller orders): two calls that overlap
- * in time race on the id lists.  One host thread at a time, process-wide.  No
+ * in time race on the id lists.  Host threads that call at the same time take
+ * turns on a lock (the enqueue order is then theirs to define).  No
  * KV_EBUSY tracking: ordering against other work on the same blocks is the
  * stream's order.  The call may be recorded into a HIP graph (stream capture)
  * once one call on that device has been made outside any capture (the first

@@ -22,6 +22,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1338,6 +1339,10 @@ int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, voi
 {
     if (!config_ok(cfg) || !hbm_cache || !host_pool) return KV_EINVAL;
     if (cfg->path != KV_PATH_AUTO && cfg->path != KV_PATH_FUSED) return KV_EUNSUP;
+    // the host-side arrays (sorted copies, the argument chunk, the address table) are the
+    // process's, not the call's: callers on several threads take turns
+    static std::mutex turn;
+    std::lock_guard<std::mutex> hold(turn);
     int rc = admit_static(cfg, oi, os, no, ii, is, ni);
     if (rc != KV_OK) return rc;
     // an engine that exists only on this stack frame, so that the launch helpers
