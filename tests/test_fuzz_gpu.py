@@ -46,7 +46,8 @@ def elems16(sh, n_blocks):
 @pytest.mark.parametrize("seed", range(16))
 def test_random_cases_match_the_oracle(seed):
     rng = np.random.default_rng(7000 + seed)
-    for k in range(25):
+    ran = moved = 0
+    for k in range(60):
         sh, layout, path, kw = random_case(rng)
         cache = rng.integers(0, 65536, elems16(sh, sh.n_hbm_blocks), dtype=np.uint16)
         pool = rng.integers(0, 65536, elems16(sh, sh.n_host_slots), dtype=np.uint16)
@@ -67,6 +68,9 @@ def test_random_cases_match_the_oracle(seed):
             try:
                 case.rotate(rot)
                 case.check()            # waits, then compares every byte
+                moved += n_out + n_in
             except AssertionError as ex:
                 raise AssertionError(f"{what}, step {step}, {n_out} out / {n_in} in: {ex}") from ex
         case.close()
+        ran += 1
+    assert ran >= 50 and moved > 300, (ran, moved)
