@@ -210,3 +210,39 @@ def test_replays_of_a_captured_call():
         assert torch.equal(pv[torch.from_numpy(rot.out_slots).long()], fresh.cpu().permute(2, 0, 1, 3, 4, 5)), f"replay {k}: out"
         assert torch.equal(dv[:, :, in_ids].cpu().permute(2, 0, 1, 3, 4, 5), incoming), f"replay {k}: in"
     case.close()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_cases_match_the_oracle(seed):
+    """Random small shapes, layouts and launch knobs through kv_rotate_static, two or
+    three calls each on one stream without a wait in between, against the oracle."""
+    rng = np.random.default_rng(8100 + seed)
+    for k in range(40):
+        sh = W.KVShape(int(rng.integers(1, 5)), int(rng.integers(1, 4)), int(rng.choice([4, 8, 20, 40, 64])),
+                       int(rng.integers(1, 8)), n_hbm_blocks=int(rng.integers(6, 40)), n_host_slots=int(rng.integers(6, 40)))
+        layout = int(rng.choice([B.KV_HOST_BLOCK_FIRST, B.KV_HOST_LAYER_FIRST]))
+        hbm_layout = int(rng.choice([B.KV_HBM_LAYER_FIRST, B.KV_HBM_BLOCK_FIRST]))
+        kw = dict(hbm_layout=hbm_layout)
+        if rng.random() < 0.4:
+            kw["vecs_per_lane"] = int(rng.choice([1, 2, 4, 8]))
+        if rng.random() < 0.4:
+            kw["max_copy_wgs"] = int(rng.choice([1, 3, 40]))
+        n16 = lambda nb: sh.n_layers * 2 * nb * sh.block_size * sh.n_kv_heads * sh.head_dim
+        cache = rng.integers(0, 65536, n16(sh.n_hbm_blocks), dtype=np.uint16)
+        pool = rng.integers(0, 65536, n16(sh.n_host_slots), dtype=np.uint16)
+        st = StaticSide(sh, layout, cache, pool, **kw)
+        oshape = O.shape_of(sh, layout, hbm_layout)
+        for step in range(int(rng.integers(2, 4))):
+            cap = min(sh.n_hbm_blocks, sh.n_host_slots)
+            n_out = int(rng.integers(0, cap // 2 + 1))
+            n_in = int(rng.integers(0, cap - n_out - cap // 4 + 1))
+            ids = rng.permutation(sh.n_hbm_blocks)[:n_out + n_in].astype(np.int32)
+            slots = rng.permutation(sh.n_host_slots)[:n_out + n_in].astype(np.int32)
+            rot = W.Rotation(ids[:n_out], slots[:n_out], ids[n_out:], slots[n_out:])
+            st.rotate(rot)
+            assert O.rotate(oshape, cache.view(np.uint8), pool.view(np.uint8), rot.out_ids, rot.out_slots,
+                            rot.in_ids, rot.in_slots) == 0
+        got_cache, got_pool = st.images()
+        what = f"seed {seed} case {k}: {sh}, layout {layout}, {kw}"
+        assert np.array_equal(got_cache, cache), what + ": cache"
+        assert np.array_equal(got_pool, pool), what + ": pool"
