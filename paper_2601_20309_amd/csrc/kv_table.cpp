@@ -17,16 +17,17 @@ namespace {
 struct TableReq {
     bool used = false, resident = false;
     int32_t len = 0;
+    int32_t n_full = 0;  // blocks in state FULL (filled, copy to DRAM not yet issued)
     std::vector<int32_t> hbm, slot, state;
 };
 
-// The ids that are free, handed out lowest first.  One bit per id, plus one bit
-// per 64-id word that says "this word has a free id", so that the lowest free id
-// is two scans of a few words (a 288 GB cache of 2 MiB blocks is 2200 words and
-// 35 summary words).  While a journal is open every change is noted and can be
-// taken back, which is how a rotation the engine refuses is undone without
-// copying the set.
-class FreeIds {
+// A set of ids read lowest first: the free blocks, the free slots, the requests
+// that have FULL blocks.  One bit per id, plus one bit per 64-id word that says
+// "this word has a member", so that the lowest member is two scans of a few
+// words (a 288 GB cache of 2 MiB blocks is 2200 words and 35 summary words).
+// While a journal is open every change is noted and can be taken back, which is
+// how a rotation the engine refuses is undone without copying the set.
+class IdSet {
   public:
     void reset(int32_t n)
     {
@@ -39,13 +40,25 @@ class FreeIds {
     size_t size() const { return count_; }
     bool empty() const { return count_ == 0; }
     void push(int32_t id) { flip(id, true); }
-    // lowest free id; the set must not be empty
-    int32_t top() const
+    void remove(int32_t id) { flip(id, false); }
+    // lowest member, -1 if there is none
+    int32_t top() const { return next(0); }
+    // lowest member >= from, -1 if there is none
+    int32_t next(int32_t from) const
     {
-        for (size_t a = 0; a < any_.size(); a++) {
-            if (!any_[a]) continue;
-            const size_t w = a * 64 + (size_t)__builtin_ctzll(any_[a]);
-            return (int32_t)(w * 64 + (size_t)__builtin_ctzll(bits_[w]));
+        size_t w = (size_t)from / 64;
+        if (w >= bits_.size()) return -1;
+        const uint64_t here = bits_[w] & (~0ull << ((size_t)from % 64));
+        if (here) return (int32_t)(w * 64 + (size_t)__builtin_ctzll(here));
+        // the words behind w: the summary bits say which of them have members
+        for (size_t nw = w + 1; nw < bits_.size();) {
+            const size_t a = nw / 64;
+            const uint64_t m = any_[a] & (~0ull << (nw % 64));
+            if (m) {
+                w = a * 64 + (size_t)__builtin_ctzll(m);
+                return (int32_t)(w * 64 + (size_t)__builtin_ctzll(bits_[w]));
+            }
+            nw = (a + 1) * 64;
         }
         return -1;
     }
@@ -68,12 +81,12 @@ class FreeIds {
     }
 
   private:
-    void flip(int32_t id, bool to_free)
+    void flip(int32_t id, bool to_member)
     {
         const size_t w = (size_t)id / 64;
         const uint64_t m = 1ull << ((size_t)id % 64);
-        if (to_free == ((bits_[w] & m) != 0)) return;  // already so
-        if (to_free) {
+        if (to_member == ((bits_[w] & m) != 0)) return;  // already so
+        if (to_member) {
             bits_[w] |= m;
             any_[w / 64] |= 1ull << (w % 64);
             count_++;
@@ -82,11 +95,11 @@ class FreeIds {
             if (!bits_[w]) any_[w / 64] &= ~(1ull << (w % 64));
             count_--;
         }
-        if (open_) journal_.emplace_back(id, to_free);
+        if (open_) journal_.emplace_back(id, to_member);
     }
     std::vector<uint64_t> bits_, any_;
     size_t count_ = 0;
-    std::vector<std::pair<int32_t, bool>> journal_;  // (id, became free)
+    std::vector<std::pair<int32_t, bool>> journal_;  // (id, became a member)
     bool open_ = false;
 };
 
@@ -96,7 +109,8 @@ struct kv_table {
     kv_engine *e = nullptr;
     int32_t max_req = 0;
     std::vector<TableReq> req;
-    FreeIds free_hbm, free_slot;
+    IdSet free_hbm, free_slot;
+    IdSet with_full;  // requests (resident ones) that have blocks in state FULL: the eager step's work list
     kv_table_counts cnt{};
     std::vector<int32_t> oi, os, ii, is, held, seen;
     // What a rotation had before it started, kept until its transfer is accepted:
@@ -119,6 +133,7 @@ void begin_undo(kv_table *t)
 {
     t->free_hbm.open_journal();
     t->free_slot.open_journal();
+    t->with_full.open_journal();
     t->undo_cnt = t->cnt;
     t->undo_req.clear();
 }
@@ -133,6 +148,7 @@ void end_undo(kv_table *t, bool ok)
     t->undo_req.clear();
     t->free_hbm.close_journal(ok);
     t->free_slot.close_journal(ok);
+    t->with_full.close_journal(ok);
     if (!ok) t->cnt = t->undo_cnt;
 }
 
@@ -154,6 +170,7 @@ int kv_table_create(kv_table **out, kv_engine *e, int32_t max_requests)
     t->req.resize((size_t)max_requests);
     t->free_hbm.reset(e->cfg.n_hbm_blocks);
     t->free_slot.reset(e->cfg.n_host_slots);
+    t->with_full.reset(max_requests);
     for (int32_t i = 0; i < e->cfg.n_hbm_blocks; i++) t->free_hbm.push(i);
     for (int32_t i = 0; i < e->cfg.n_host_slots; i++) t->free_slot.push(i);
     t->seen.assign((size_t)max_requests, 0);
@@ -197,8 +214,14 @@ int kv_table_append(kv_table *t, int32_t rq, int32_t n_tokens, int32_t *new_ids,
         if (new_ids) new_ids[k] = b;
     }
     r.len = (int32_t)new_len;
-    for (size_t i = 0; i < r.hbm.size(); i++)
-        if ((int64_t)(i + 1) * P <= r.len && r.state[i] == KV_BLOCK_DIRTY) r.state[i] = KV_BLOCK_FULL;
+    // blocks that this call filled up: the former tail and the new ones, but for the new tail
+    for (size_t i = old_n > 0 ? (size_t)old_n - 1 : 0; i < r.hbm.size(); i++) {
+        if ((int64_t)(i + 1) * P <= r.len && r.state[i] == KV_BLOCK_DIRTY) {
+            r.state[i] = KV_BLOCK_FULL;
+            r.n_full++;
+        }
+    }
+    if (r.n_full > 0) t->with_full.push(rq);
     if (n_new) *n_new = (int32_t)need;
     return KV_OK;
 }
@@ -210,9 +233,8 @@ static void pick_eager(kv_table *t, int32_t budget, std::vector<std::pair<int32_
                        std::vector<int32_t> &fresh)
 {
     int32_t n = 0;
-    for (int32_t q = 0; q < t->max_req && n < budget; q++) {
+    for (int32_t q = t->with_full.top(); q >= 0 && n < budget; q = t->with_full.next(q + 1)) {
         TableReq &r = t->req[(size_t)q];
-        if (!r.used || !r.resident) continue;
         for (size_t i = 0; i < r.hbm.size() && n < budget; i++) {
             if (r.state[i] != KV_BLOCK_FULL) continue;
             int32_t sl = r.slot[i];
@@ -238,6 +260,7 @@ static void mark_synced(kv_table *t, const std::vector<std::pair<int32_t, size_t
         TableReq &r = t->req[(size_t)picked[k].first];
         r.slot[picked[k].second] = t->os[first + k];
         r.state[picked[k].second] = KV_BLOCK_SYNCED;
+        if (--r.n_full == 0) t->with_full.remove(picked[k].first);
     }
 }
 
@@ -316,6 +339,8 @@ static bool leave_hbm(kv_table *t, int32_t q, int64_t &released)
         r.state[b] = KV_BLOCK_HOST;
     }
     r.resident = false;
+    r.n_full = 0;
+    t->with_full.remove(q);
     return true;
 }
 
@@ -405,6 +430,7 @@ int kv_table_finish(kv_table *t, int32_t rq)
         if (r.hbm[b] >= 0) t->free_hbm.push(r.hbm[b]);
         if (r.slot[b] >= 0) t->free_slot.push(r.slot[b]);
     }
+    t->with_full.remove(rq);
     r = TableReq{};
     return KV_OK;
 }
