@@ -650,12 +650,13 @@ def interference():
     cache = _cache(shape)
     print(f"\nhipMemcpyAsync pinned peaks: D2H {link['d2h']:.2f}, H2D {link['h2d']:.2f} GB/s\n")
     print("| rotation path | copy WGs x lanes | rotation alone GB/s (out+in) | rotation beside reader GB/s | "
-          "reader alone TB/s | reader beside rotation TB/s |")
-    print("|---|---|---|---|---|---|")
+          "reader alone TB/s | reader beside rotation TB/s | reader time lost, ms per GiB moved |")
+    print("|---|---|---|---|---|---|---|")
     for path, wgs, lanes, contiguous in [(B.KV_PATH_FUSED, 0, 0, False), (B.KV_PATH_FUSED, 192, 64, False),
                                          (B.KV_PATH_FUSED, 144, 64, False), (B.KV_PATH_FUSED, 96, 64, False),
                                          (B.KV_PATH_FUSED, 80, 64, False), (B.KV_PATH_FUSED, 64, 64, False),
-                                         (B.KV_PATH_FUSED, 28, 256, False),
+                                         (B.KV_PATH_FUSED, 28, 256, False), (B.KV_PATH_FUSED, 16, 448, False),
+                                         (B.KV_PATH_FUSED, 8, 896, False),
                                          (B.KV_PATH_SDMA_STAGED, 0, 0, True), (B.KV_PATH_DMA_BLOCKS, 0, 0, False)]:
         rot = W.config_rotation(name, contiguous_slots=contiguous)
         named = np.zeros(shape.n_hbm_blocks, bool)
@@ -702,12 +703,16 @@ def interference():
         ms_both = statistics.median(both)
         launch = ("no kernel, block-first cache" if path == B.KV_PATH_DMA_BLOCKS else "pack / unpack kernels"
                   if path != B.KV_PATH_FUSED else f"{wgs} x {lanes}" if wgs else "default (112 x 64)")
+        # what the co-runner pays: the part of the rotation's duration in which it got nothing done
+        rb = statistics.median(read_both)
+        lost = ms_both * (1 - rb / read_alone) / (moved / 2**30)
         print(f"| {B.PATH_NAMES[path]} | {launch} | {moved / ms_alone / 1e6:.2f} | {moved / ms_both / 1e6:.2f} | "
-              f"{read_alone:.2f} | {statistics.median(read_both):.2f} |", flush=True)
+              f"{read_alone:.2f} | {rb:.2f} | {lost:.2f} |", flush=True)
         eng.kv_destroy()
     # one direction at a time (what the eager step and a plain resumption issue), default shapes
-    print("\n| one direction, default shape | alone GB/s | beside reader GB/s | reader alone TB/s | reader beside TB/s |")
-    print("|---|---|---|---|---|")
+    print("\n| one direction, default shape | alone GB/s | beside reader GB/s | reader alone TB/s | reader beside TB/s | "
+          "reader time lost, ms per GiB moved |")
+    print("|---|---|---|---|---|---|")
     rot = W.config_rotation(name, contiguous_slots=False)
     inv = rot.inverse()
     named = np.zeros(shape.n_hbm_blocks, bool)
@@ -744,8 +749,10 @@ def interference():
                     acc += p
                 inside = inside[1:] or pm2
                 read_both.append(read_bytes * len(inside) / sum(inside) / 1e9)
+        rb, ra = statistics.median(read_both), read_bytes / ms_pass / 1e9
+        lost = statistics.median(both) * (1 - rb / ra) / (n_moved / 2**30)
         print(f"| {label} | {n_moved / ms_alone / 1e6:.2f} | {n_moved / statistics.median(both) / 1e6:.2f} | "
-              f"{read_bytes / ms_pass / 1e9:.2f} | {statistics.median(read_both):.2f} |", flush=True)
+              f"{ra:.2f} | {rb:.2f} | {lost:.2f} |", flush=True)
     eng.kv_destroy()
 
 
