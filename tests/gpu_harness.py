@@ -1,5 +1,7 @@
 """Helpers for the GPU parity tests: run one call sequence through the C ABI
 and through the oracle on the same seeded images, and compare every byte."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import torch
 
@@ -81,6 +83,18 @@ def make_case(name_or_shape, layout, path, rot=None, seed=None, **kw):
     return GpuCase(shape, layout, path, cache, pool, **kw), rot
 
 
+_WORKERS = 8
+_pool = ThreadPoolExecutor(_WORKERS)
+
+
+def _over(n, fn):
+    """fn(a, b) on slices [a, b) that tile range(n), on the worker threads (NumPy
+    copies and comparisons of large arrays release the interpreter lock);
+    returns the results in order."""
+    step = -(-n // _WORKERS)
+    return list(_pool.map(lambda a: fn(a, min(n, a + step)), range(0, n, step)))
+
+
 class BigCase:
     """Full-size check that needs little host memory.
 
@@ -110,11 +124,12 @@ class BigCase:
         self.say(f"{name}: cache of {O.cache_bytes(self.oshape) >> 30} GiB drawn")
         self.eng = B.Engine(self.cfg, self.cache.data_ptr())
         self.pool_u8 = self.eng.host_pool_array()
-        self.pool_u8[:] = self.FILL
+        _over(self.pool_u8.size, lambda a, b: self.pool_u8[a:b].fill(self.FILL))
         self.say(f"{name}: pool of {O.pool_bytes(self.oshape) >> 30} GiB filled")
         self.ref_cache = np.empty(O.cache_bytes(self.oshape), dtype=np.uint8)   # lazily backed
         self.ref_pool = np.empty(O.pool_bytes(self.oshape), dtype=np.uint8)
         self.touched_blocks, self.touched_slots = set(), set()
+        self._pinned = None
 
     # views [L,2,N,P,H,D] (uint16) of the host images and the pinned pool
     def _cv(self):
@@ -129,9 +144,17 @@ class BigCase:
             yield items[c0:c0 + self.per_piece]
 
     def _device_blocks(self, ids):
-        """[L,2,len(ids),P,H,D] uint16 copy of the named blocks as the GPU holds them."""
+        """[L,2,len(ids),P,H,D] uint16 copy of the named blocks as the GPU holds them,
+        in a pinned buffer that the next call overwrites."""
         idx = torch.tensor(ids, device="cuda")
-        return self.cache.view(torch.int16)[:, :, idx].cpu().numpy().view(np.uint16)
+        got = self.cache.view(torch.int16)[:, :, idx]
+        if self._pinned is None:
+            self._pinned = torch.empty(self.per_piece * O.block_bytes(self.oshape) // 2, dtype=torch.int16,
+                                       pin_memory=True)
+        host = self._pinned[:got.numel()].view(got.shape)
+        host.copy_(got)
+        torch.cuda.synchronize()
+        return host.numpy().view(np.uint16)
 
     def stage(self, slots, seed_offset=50):
         """Put seeded blocks into host slots (pinned pool and reference alike)."""
@@ -140,8 +163,12 @@ class BigCase:
         for part in self._pieces(slots):
             blocks = W.staged_blocks(self.shape, len(part), self.seed + seed_offset + k, device="cuda")
             arr = blocks.view(torch.int16).cpu().numpy().view(np.uint16).transpose(1, 2, 0, 3, 4, 5)
-            self._pv(self.pool_u8)[:, :, part] = arr
-            self._pv(self.ref_pool)[:, :, part] = arr
+            pv, rv = self._pv(self.pool_u8), self._pv(self.ref_pool)
+
+            def put(a, b):      # layers [a, b)
+                pv[a:b, :, part] = arr[a:b]
+                rv[a:b, :, part] = arr[a:b]
+            _over(self.shape.n_layers, put)
             k += 1
         self.touched_slots.update(int(s) for s in slots)
         self.say(f"{self.name}: {len(slots)} slots staged")
@@ -152,12 +179,20 @@ class BigCase:
         stay among the blocks check() compares with the regenerated image."""
         new_b = [int(b) for b in ids if int(b) not in self.touched_blocks]
         for part in self._pieces(new_b):
-            self._cv()[:, :, part] = self._device_blocks(part)
+            dev, cv = self._device_blocks(part), self._cv()
+
+            def put(a, b):
+                cv[a:b, :, part] = dev[a:b]
+            _over(self.shape.n_layers, put)
         if not read_only:
             self.touched_blocks.update(new_b)
         new_s = [int(s) for s in slots if int(s) not in self.touched_slots]
         for part in self._pieces(new_s):
-            self._pv(self.ref_pool)[:, :, part] = self._pv(self.pool_u8)[:, :, part]
+            pv, rv = self._pv(self.pool_u8), self._pv(self.ref_pool)
+
+            def put(a, b):
+                rv[a:b, :, part] = pv[a:b, :, part]
+            _over(self.shape.n_layers, put)
         self.touched_slots.update(new_s)
         if new_b or new_s:
             self.say(f"{self.name}: {len(new_b)} blocks and {len(new_s)} slots mirrored on the host")
@@ -173,12 +208,15 @@ class BigCase:
         tb = sorted(self.touched_blocks)
         ts = sorted(self.touched_slots)
         # named blocks and slots: against the oracle
+        L = self.shape.n_layers
         for ids in self._pieces(tb):
-            assert np.array_equal(self._device_blocks(ids), self._cv()[:, :, ids]), \
+            dev, cv = self._device_blocks(ids), self._cv()
+            assert all(_over(L, lambda a, b: np.array_equal(dev[a:b], cv[a:b, :, ids]))), \
                 "named HBM blocks differ from the oracle"
         self.say(f"{self.name}: {len(tb)} named blocks equal the oracle's")
         for sl in self._pieces(ts):
-            assert np.array_equal(self._pv(self.pool_u8)[:, :, sl], self._pv(self.ref_pool)[:, :, sl]), \
+            pv, rv = self._pv(self.pool_u8), self._pv(self.ref_pool)
+            assert all(_over(L, lambda a, b: np.array_equal(pv[a:b, :, sl], rv[a:b, :, sl]))), \
                 "named host slots differ from the oracle"
         self.say(f"{self.name}: {len(ts)} named slots equal the oracle's")
         # every other block: against a regenerated image
@@ -194,10 +232,11 @@ class BigCase:
         pv = self._pv(self.pool_u8)
         pat = np.uint16(self.FILL * 0x0101)
         for sl in self._pieces(np.flatnonzero(mask)):
-            assert (pv[:, :, sl] == pat).all(), "an un-named slot changed"
+            assert all(_over(L, lambda a, b: bool((pv[a:b, :, sl] == pat).all()))), "an un-named slot changed"
         self.say(f"{self.name}: every other block and slot unchanged")
 
     def close(self):
         self.eng.kv_destroy()
         del self.cache
+        self._pinned = None
         torch.cuda.empty_cache()

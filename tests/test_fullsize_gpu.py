@@ -2,6 +2,7 @@
 (default config: AUTO path, block-first pool, library-owned pool and streams)."""
 import numpy as np
 import pytest
+import torch
 
 from oracle import kv_oracle as O
 from paper_2601_20309_amd import binding as B
@@ -24,6 +25,35 @@ def test_llama3_8b_rotation_full_size():
     assert st["bytes_out"] == st["bytes_in"] == 256 << 20
     case.rotate(rot.inverse())      # what bench.py alternates with
     case.check()
+    case.close()
+
+
+@pytest.mark.parametrize("where", ["named block", "named slot", "other block", "other slot"])
+def test_the_full_size_check_notices_one_wrong_byte(where):
+    """The check itself: one byte changed on the CPU side (in the oracle's images, or in a
+    slot or block that no list names) after a correct rotation makes it fail."""
+    case = BigCase("llama3_8b")
+    rot = W.config_rotation("llama3_8b")
+    case.stage(rot.in_slots)
+    case.rotate(rot)
+    case.check()
+    named_b = np.zeros(case.shape.n_hbm_blocks, bool)
+    named_b[rot.out_ids] = named_b[rot.in_ids] = True
+    named_s = np.zeros(case.shape.n_host_slots, bool)
+    named_s[rot.out_slots] = named_s[rot.in_slots] = True
+    last_layer = case.shape.n_layers - 1
+    if where == "named block":        # the oracle's image of the last block swapped in, last layer, V, last element
+        case._cv()[last_layer, 1, rot.in_ids[-1], -1, -1, -1] ^= 1
+    elif where == "named slot":
+        case._pv(case.ref_pool)[last_layer, 0, rot.out_slots[-1], 0, 0, 0] ^= 0x100
+    elif where == "other block":      # a block no list names, changed on the device
+        b = int(np.flatnonzero(~named_b)[-1])
+        case.cache.view(torch.int16)[last_layer, 1, b, -1, -1, -1] += 1
+    else:                             # a slot no list names, changed in the pinned pool
+        sl = int(np.flatnonzero(~named_s)[-1])
+        case._pv(case.pool_u8)[last_layer, 1, sl, -1, -1, -1] ^= 1
+    with pytest.raises(AssertionError):
+        case.check()
     case.close()
 
 
