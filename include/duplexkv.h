@@ -209,6 +209,15 @@ int kv_rotate_static(const kv_config *cfg, void *hbm_cache, void *host_pool, voi
  * coherent for CPU reads.  Closes the interval kv_last_stats() reports. */
 int kv_wait(kv_engine *engine);
 
+/* The same question without blocking, for a loop that polls between other work
+ * (the engine loop of Section 4.3.2 prepares iteration t+1 while transfers run):
+ * KV_OK when everything enqueued so far is done (kv_wait would return at once;
+ * blocks swapped in may be read, host slots written may be read by the CPU),
+ * KV_EBUSY while something still runs.  Changes nothing: the stats interval
+ * stays open until kv_wait, and calls that KV_EBUSY-refuse lists overlapping
+ * un-waited work keep doing so until kv_wait. */
+int kv_query(kv_engine *engine);
+
 /*
  * Layer by layer (north_star: "per-layer chunking so that the transfers
  * overlap"; the paper overlaps the rotation for iteration t+1 with the execution

@@ -27,7 +27,7 @@ KV_PATH_AUTO, KV_PATH_SDMA_STAGED, KV_PATH_ZEROCOPY, KV_PATH_NAIVE, KV_PATH_FUSE
 PATH_NAMES = {0: "auto", 1: "sdma_staged", 2: "zerocopy", 3: "naive", 4: "fused", 5: "dma_blocks"}
 
 EXPORTS = ["kv_seg_bytes", "kv_block_bytes", "kv_cache_bytes", "kv_pool_bytes", "kv_validate",
-           "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_rotate_static", "kv_wait", "kv_stream_wait_layer", "kv_wait_layer",
+           "kv_create", "kv_destroy", "kv_swap_out", "kv_swap_in", "kv_rotate", "kv_rotate_static", "kv_wait", "kv_query", "kv_stream_wait_layer", "kv_wait_layer",
            "kv_host_pool", "kv_last_stats", "kv_probe_link", "kv_reader_start", "kv_reader_wait",
            "kv_table_create", "kv_table_destroy", "kv_table_append", "kv_table_eager", "kv_table_rotate", "kv_table_rotate_eager",
            "kv_table_finish", "kv_table_blocks", "kv_table_get_counts", "kv_sched_vlt", "kv_sched_lvf",
@@ -94,6 +94,8 @@ def _load() -> C.CDLL:
     L.kv_rotate_static.argtypes = [pcfg, C.c_void_p, C.c_void_p, C.c_void_p, p32, p32, C.c_int32, p32, p32, C.c_int32]
     L.kv_wait.restype = C.c_int
     L.kv_wait.argtypes = [C.c_void_p]
+    L.kv_query.restype = C.c_int
+    L.kv_query.argtypes = [C.c_void_p]
     L.kv_stream_wait_layer.restype = C.c_int
     L.kv_stream_wait_layer.argtypes = [C.c_void_p, C.c_void_p, C.c_int32]
     L.kv_wait_layer.restype = C.c_int
@@ -256,6 +258,9 @@ class Engine:
 
     def kv_wait(self) -> int:
         return lib.kv_wait(self._h)
+
+    def kv_query(self) -> int:
+        return lib.kv_query(self._h)
 
     def kv_stream_wait_layer(self, stream: int, layer: int) -> int:
         return lib.kv_stream_wait_layer(self._h, C.c_void_p(stream or None), layer)

@@ -1280,6 +1280,23 @@ int kv_wait(kv_engine *e)
     return KV_OK;
 }
 
+int kv_query(kv_engine *e)
+{
+    if (!e) return KV_EINVAL;
+    if (e->sticky != KV_OK) return e->sticky;
+    for (int side = 0; side < 2; side++) {
+        const bool pending = side == 0 ? e->out_pending : e->in_pending;
+        if (!pending) continue;
+        const hipError_t q = hipStreamQuery(side == 0 ? e->s_out : e->s_in);
+        if (q == hipErrorNotReady) {
+            (void)hipGetLastError();  // not an error: forget it
+            return KV_EBUSY;
+        }
+        HIPTRY(e, q);
+    }
+    return KV_OK;
+}
+
 // The events behind which `layer` of the most recent transfer call is complete:
 // its chunk's events if that call ran layer by layer, else the call's end events.
 static int layer_events(kv_engine *e, int32_t layer, hipEvent_t (&out)[2])

@@ -343,3 +343,35 @@ def test_racing_calls_are_refused_and_joined_calls_are_not():
     case.swap_out(rot.in_ids[:3], rot.out_slots[:3])   # after a join: ordered, although one stream only
     case.check()
     case.close()
+
+
+@pytest.mark.parametrize("path", [B.KV_PATH_AUTO, B.KV_PATH_ZEROCOPY, B.KV_PATH_SDMA_STAGED])
+def test_query_polls_without_blocking(path):
+    """kv_query: KV_OK with nothing in flight, KV_EBUSY right behind the enqueue of
+    128 + 128 MiB (which takes milliseconds), KV_OK some time later without any
+    blocking call; the bytes are then in place, and the stats interval is still
+    open for kv_wait to close."""
+    import time
+    sh = W.KVShape(32, 8, 128, 16, n_hbm_blocks=300, n_host_slots=160)       # 2 MiB blocks
+    rot = W.simple_rotation(sh, 64, 64, seed=5)
+    case, _ = make_case(sh, B.KV_HOST_BLOCK_FIRST, path, rot=rot)
+    assert case.eng.kv_query() == 0
+    assert case.eng.kv_rotate(rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots) == 0
+    first = case.eng.kv_query()
+    deadline, polls = time.time() + 20, 0
+    while case.eng.kv_query() == B.KV_EBUSY:
+        polls += 1
+        assert time.time() < deadline, "the transfer never finished"
+        time.sleep(0.0002)
+    assert case.eng.kv_query() == 0
+    assert first == B.KV_EBUSY and polls > 0, "a transfer of milliseconds was done before the call returned"
+    assert O.rotate(case.oshape, case.ref_cache.view(np.uint8), case.ref_pool.view(np.uint8),
+                    rot.out_ids, rot.out_slots, rot.in_ids, rot.in_slots) == 0
+    # in place before any kv_wait: the pool as the CPU sees it, the cache as a copy sees it
+    assert np.array_equal(case.pool_u8.view(np.uint16), case.ref_pool)
+    assert np.array_equal(case.dev_cache.cpu().numpy().view(np.uint16), case.ref_cache)
+    assert case.eng.kv_wait() == 0
+    st = case.eng.kv_last_stats()
+    assert st["bytes_out"] == st["bytes_in"] == 64 * (2 << 20)
+    assert case.eng.kv_query() == 0
+    case.close()
