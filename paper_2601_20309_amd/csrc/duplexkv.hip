@@ -1570,13 +1570,12 @@ int kv_reader_start(kv_engine *e, const int32_t *ids, int32_t n, int32_t passes,
         HIPTRY(e, hipMemcpyAsync(e->read_ids, e->read_ids_host, (size_t)n * sizeof(int32_t),
                                  hipMemcpyHostToDevice, e->s_read));
     }
-    // Six of these workgroups fill a CU's registers.  Measured per pass over 37.5 GiB:
-    // 4 per CU 5.74 TB/s, 5 per CU 6.40, 5.5 per CU 6.51, 6 and more 6.45 (the
-    // surplus only queues).  From 6 per CU on the persistent workgroups also hold
-    // every register of the chip for a whole pass (~6 ms), so that no other
-    // kernel's waves can start before the pass ends, which no model execution made
-    // of many short kernels would do to a rotation; 5.5 per CU is the fastest and
-    // leaves that room.
+    // Measured per pass over 37.5 GiB, TB/s by workgroups per CU (claims of 32
+    // tiles): 4 -> 5.70, 5 -> 6.56, 5.5 -> 6.68, 6 -> 6.75, 8 -> 6.85.  From 6 per
+    // CU on the persistent workgroups hold so much of every CU for a whole pass
+    // (~6 ms) that another kernel's waves wait for the pass to end before they
+    // start, which no model execution made of many short kernels would do to a
+    // rotation; 5.5 per CU gives up 2 % and leaves that room.
     int wgs = 11 * (e->n_cus > 0 ? e->n_cus : 256) / 2;
     if (max_wgs > 0) wgs = std::min(wgs, (int)max_wgs);
     wgs = (int)std::min<uint32_t>((uint32_t)wgs, std::max<uint32_t>(p.tiles, 1u));

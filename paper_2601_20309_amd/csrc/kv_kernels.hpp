@@ -412,7 +412,10 @@ __global__ __launch_bounds__(kThreads) void kv_stage_kernel(const StageParams p,
 // chip streams one contiguous front of the cache, and a CU that is slowed by a
 // co-running kernel simply claims less (with a fixed share per workgroup the
 // slowest CU sets the pace of the whole pass).  One short-lived workgroup per
-// few tiles, left to the hardware dispatcher, measured 27 % slower.
+// few tiles, left to the hardware dispatcher, measured 27 % slower.  The loads
+// are non-temporal (nothing is read twice): worth 3 % when the blocks come in
+// random order and 16 % on the block-first cache, whose segments lie a whole
+// block apart (5.54 -> 6.43 TB/s), nothing on consecutive blocks.
 struct ReadParams {
     const uint8_t *hbm;
     const int32_t *ids;
@@ -427,7 +430,13 @@ struct ReadParams {
     unsigned int *next;      // tile counter of this pass, zero at launch
 };
 
-constexpr uint32_t kReadClaim = 4;  // tiles a workgroup claims per turn
+// Tiles a workgroup claims per turn.  One counter serves the whole chip, and at
+// 6.5 TB/s a 32 KiB tile lasts 5 ns: measured over 37.5 GiB, 5.5 workgroups per
+// CU, TB/s by claim size: 2 -> 4.65, 4 -> 6.51, 8 -> 6.65, 16 -> 6.74, 32 -> 6.68,
+// 64 -> 6.62, 128 -> 6.53 (beyond 16 the pass ends more raggedly than the counter
+// saves).
+constexpr uint32_t kReadClaim = 16;
+constexpr uint32_t kReadClaimTail = 4;  // within the last 2 * kReadClaim tiles per workgroup of a pass
 
 template <int U>
 __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
@@ -435,13 +444,19 @@ __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
     const uint32_t tid = threadIdx.x;
     unsigned long long sum = 0;
     __shared__ uint32_t claimed;
+    // near the end of the pass the claims get short, so that the workgroups end
+    // within a few tiles of each other (a long last claim on a slowed CU would
+    // hold up the whole pass)
+    const uint32_t tail = 2u * kReadClaim * gridDim.x, short_from = p.tiles > tail ? p.tiles - tail : 0u;
+    uint32_t want = short_from ? kReadClaim : kReadClaimTail;
     for (;;) {
-        if (tid == 0) claimed = atomicAdd(p.next, kReadClaim);
+        if (tid == 0) claimed = atomicAdd(p.next, want);
         __syncthreads();
         const uint32_t t0 = claimed;
         __syncthreads();
         if (t0 >= p.tiles) break;
-        const uint32_t t1 = min(p.tiles, t0 + kReadClaim);
+        const uint32_t t1 = min(p.tiles, t0 + want);
+        want = t1 < short_from ? kReadClaim : kReadClaimTail;
         for (uint32_t t = t0; t < t1; t++) {
         const uint32_t segidx = t / p.tiles_per_seg;
         const uint32_t tin = t - segidx * p.tiles_per_seg;
@@ -454,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void kv_reader_kernel(const ReadParams p)
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const uint32_t vi = v0 + u * kThreads;
-            v[u] = vi < p.vec_per_seg ? src[vi] : u32x4{0u, 0u, 0u, 0u};
+            v[u] = vi < p.vec_per_seg ? __builtin_nontemporal_load(src + vi) : u32x4{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int u = 0; u < U; u++)
