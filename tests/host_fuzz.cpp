@@ -116,6 +116,8 @@ int dkv::drain(kv_engine *) { return KV_OK; }
 // ---- table fuzz
 namespace {
 
+constexpr int32_t kCap = 256;  // blocks a request of the fuzz may reach
+
 struct Pair {
     kv_table *lib = nullptr;
     okvt *ora = nullptr;
@@ -128,8 +130,8 @@ struct Pair {
 // The model's part: tokens [from, to) of request q get their bytes, in both caches.
 void write_tokens(Pair &p, int32_t q, int32_t from, int32_t to, std::mt19937_64 &rng)
 {
-    int32_t ids[64], n = 0;
-    CHECK(kv_table_blocks(p.lib, q, ids, nullptr, nullptr, 64, &n, nullptr) == KV_OK, "blocks");
+    int32_t ids[kCap], n = 0;
+    CHECK(kv_table_blocks(p.lib, q, ids, nullptr, nullptr, kCap, &n, nullptr) == KV_OK, "blocks");
     const uint64_t tok_bytes = g_block_bytes / (uint64_t)p.s.block_size;
     for (int32_t tkn = from; tkn < to; tkn++) {
         const int32_t b = ids[tkn / p.s.block_size];
@@ -145,11 +147,11 @@ void write_tokens(Pair &p, int32_t q, int32_t from, int32_t to, std::mt19937_64 
 
 void compare(Pair &p, long step, const char *op)
 {
-    int32_t la[64], lb[64], lc[64], oa[64], ob[64], oc[64];
+    int32_t la[kCap], lb[kCap], lc[kCap], oa[kCap], ob[kCap], oc[kCap];
     for (int32_t q = 0; q < p.max_req; q++) {
         int32_t ln = -1, on = -1, li[2] = {-1, -1}, oi[2] = {-1, -1};
-        const int rl = kv_table_blocks(p.lib, q, la, lb, lc, 64, &ln, li);
-        const int ro = okvt_blocks(p.ora, q, oa, ob, oc, 64, &on, oi);
+        const int rl = kv_table_blocks(p.lib, q, la, lb, lc, kCap, &ln, li);
+        const int ro = okvt_blocks(p.ora, q, oa, ob, oc, kCap, &on, oi);
         CHECK(rl == ro, "step %ld (%s) req %d: blocks() returned %d, oracle %d", step, op, q, rl, ro);
         if (rl != KV_OK) continue;
         CHECK(ln == on && li[0] == oi[0] && li[1] == oi[1], "step %ld (%s) req %d: n %d/%d len %d/%d resident %d/%d",
@@ -173,8 +175,11 @@ void compare(Pair &p, long step, const char *op)
     CHECK(g_pool == p.o_pool, "step %ld (%s): pool bytes differ", step, op);
 }
 
-long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_req, int32_t P)
+// reach_id: the run must hand out a block id at least this high (so that the id
+// sets of the library are exercised beyond their first words)
+long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_req, int32_t P, int32_t reach_id = 0)
 {
+    int32_t top_id = -1;
     std::mt19937_64 rng(seed);
     Pair p;
     p.s = okv_shape{1, 1, 4, P, 2, nb, ns, 0, 1};
@@ -198,13 +203,29 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
     CHECK(p.ora, "oracle create");
 
     long failed_ops = 0;
+    // a table that starts out well filled: requests of 60 blocks until the ids wanted are in use
+    for (int32_t q = 0; reach_id > 0 && top_id < reach_id; q++) {
+        CHECK(q < max_req, "not enough requests to reach block id %d", reach_id);
+        int32_t li[64], oi[64], ln = -7, on = -7;
+        const int rl = kv_table_append(p.lib, q, 60 * P, li, 64, &ln);
+        const int ro = okvt_append(p.ora, q, 60 * P, oi, 64, &on);
+        CHECK(rl == KV_OK && ro == KV_OK && ln == 60 && on == 60, "filling: %d / %d, %d / %d blocks", rl, ro, ln, on);
+        for (int32_t k = 0; k < ln; k++) {
+            CHECK(li[k] == oi[k], "filling: new id differs");
+            top_id = std::max(top_id, li[k]);
+        }
+        write_tokens(p, q, 0, 60 * P, rng);
+        p.written[(size_t)q] = 60 * P;
+        compare(p, -1, "fill");
+    }
     for (long step = 0; step < steps; step++) {
         const unsigned pick = (unsigned)(rng() % 100);
         const char *op = "";
         if (pick < 45) {  // grow or create a request
             op = "append";
             const int32_t q = (int32_t)(rng() % (uint64_t)(max_req + 1)) - (rng() % 64 == 0);  // sometimes invalid
-            const int32_t n_tok = (int32_t)(rng() % (uint64_t)(3 * P + 1)) - (rng() % 97 == 0);
+            int32_t n_tok = (int32_t)(rng() % (uint64_t)(3 * P + 1)) - (rng() % 97 == 0);
+            if (q >= 0 && q < max_req && n_tok > 0 && p.written[(size_t)q] + n_tok > (kCap - 1) * P) n_tok = 0;
             int32_t li[64], oi[64], ln = -7, on = -7;
             const int rl = kv_table_append(p.lib, q, n_tok, li, 64, &ln);
             const int ro = okvt_append(p.ora, q, n_tok, oi, 64, &on);
@@ -212,6 +233,7 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
             if (rl == KV_OK) {
                 CHECK(ln == on, "step %ld append: %d new blocks, oracle %d", step, ln, on);
                 for (int32_t k = 0; k < ln; k++) CHECK(li[k] == oi[k], "step %ld append: new id differs", step);
+                for (int32_t k = 0; k < ln; k++) top_id = std::max(top_id, li[k]);
                 write_tokens(p, q, p.written[(size_t)q], p.written[(size_t)q] + n_tok, rng);
                 p.written[(size_t)q] += n_tok;
             } else
@@ -310,6 +332,7 @@ long fuzz_table(uint64_t seed, long steps, int32_t nb, int32_t ns, int32_t max_r
     CHECK(c.copied_eager > 0 && c.copied_preempt > 0 && c.dropped_synced > 0 && c.swapped_in > 0,
           "the fuzz never reached one of the four kinds of block movement");
     CHECK(g_refused > 0, "the fuzz never refused a transfer");
+    CHECK(top_id >= reach_id, "the fuzz only reached block id %d of the %d wanted", top_id, reach_id);
     CHECK(kv_table_destroy(p.lib) == KV_OK, "destroy");
     okvt_destroy(p.ora);
     return failed_ops;
@@ -382,6 +405,9 @@ int main(int argc, char **argv)
     fuzz_table(2, steps, 9, 40, 10, 4);
     fuzz_table(3, steps, 24, 11, 10, 4);
     fuzz_table(4, steps, 16, 24, 6, 1);
+    // id sets of several words; of several summary words (ids beyond 4096)
+    fuzz_table(7, steps, 300, 500, 150, 2, 200);
+    fuzz_table(8, steps, 6000, 9000, 700, 1, 4200);
     fuzz_sched(5, rounds);
     fuzz_sched(6, rounds);
     std::printf("host fuzz ok\n");
