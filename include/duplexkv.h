@@ -62,7 +62,8 @@ extern "C" {
 
 /* ---- transfer paths ---- */
 #define KV_PATH_AUTO        0  /* engine picks: FUSED for a rotation, ZEROCOPY for one direction */
-#define KV_PATH_SDMA_STAGED 1  /* pack kernel -> staging in HBM -> hipMemcpyAsync (DMA engines), and the mirror */
+#define KV_PATH_SDMA_STAGED 1  /* pack kernel -> staging in HBM -> hipMemcpyAsync (DMA engines), and the mirror: ~10 % slower
+                                  than the kernel paths, and takes a third as much from an HBM-bound kernel running beside it */
 #define KV_PATH_ZEROCOPY    2  /* one kernel per direction, each on its own stream, reading / writing host memory directly */
 #define KV_PATH_NAIVE       3  /* one hipMemcpyAsync per segment: the baseline of Section 4.3.1, for the benchmark ladder */
 #define KV_PATH_FUSED       4  /* one kernel moves both directions, interleaved per lane: 1:1, or, when the in list is the
