@@ -214,9 +214,9 @@ int kv_wait(kv_engine *engine);
  * (the engine loop of Section 4.3.2 prepares iteration t+1 while transfers run):
  * KV_OK when everything enqueued so far is done (kv_wait would return at once;
  * blocks swapped in may be read, host slots written may be read by the CPU),
- * KV_EBUSY while something still runs.  Changes nothing: the stats interval
- * stays open until kv_wait, and calls that KV_EBUSY-refuse lists overlapping
- * un-waited work keep doing so until kv_wait. */
+ * KV_EBUSY while something still runs.  The stats interval stays open until
+ * kv_wait; once KV_OK has been returned, lists that overlap the finished work
+ * are accepted again (no KV_EBUSY for a race that can no longer happen). */
 int kv_query(kv_engine *engine);
 
 /*

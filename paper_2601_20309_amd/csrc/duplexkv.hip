@@ -1294,6 +1294,9 @@ int kv_query(kv_engine *e)
         }
         HIPTRY(e, q);
     }
+    // nothing runs any more, so nothing can race with what comes next
+    e->out_dirty = e->in_dirty = false;
+    e->hazards.join();
     return KV_OK;
 }
 

@@ -370,8 +370,13 @@ def test_query_polls_without_blocking(path):
     # in place before any kv_wait: the pool as the CPU sees it, the cache as a copy sees it
     assert np.array_equal(case.pool_u8.view(np.uint16), case.ref_pool)
     assert np.array_equal(case.dev_cache.cpu().numpy().view(np.uint16), case.ref_cache)
+    # what would have raced with the finished call is accepted now, without a kv_wait in between
+    # (on the two-stream paths the inverse is refused while the first call still runs)
+    inv = rot.inverse()
+    case.rotate(inv)
     assert case.eng.kv_wait() == 0
     st = case.eng.kv_last_stats()
-    assert st["bytes_out"] == st["bytes_in"] == 64 * (2 << 20)
+    assert st["bytes_out"] == st["bytes_in"] == 2 * 64 * (2 << 20)        # one interval: both calls
     assert case.eng.kv_query() == 0
+    case.check()
     case.close()
