@@ -331,6 +331,13 @@ int kv_table_destroy(kv_table *table);
  * tokens' KV into the request's blocks.  Tokens that land in a partly filled
  * block make it DIRTY; a block that fills up becomes FULL.  KV_ENOSPC, with
  * nothing changed, if the cache has too few free blocks.
+ * A block handed out here may be one that a preemption released while its copy
+ * to DRAM is still in flight: the caller's writes (which the engine's streams
+ * know nothing of) have to come after the transfers enqueued so far, i.e. after
+ * kv_wait(), kv_query() == KV_OK, or on a stream that waited through
+ * kv_stream_wait_layer(stream, n_layers - 1).  In the cross-iteration pipeline
+ * of Section 4.3.2 that is the case anyway: iteration t+1 starts when its
+ * rotation has landed.
  */
 int kv_table_append(kv_table *table, int32_t req, int32_t n_tokens, int32_t *new_block_ids, int32_t cap,
                     int32_t *n_new);
@@ -369,10 +376,12 @@ int kv_table_rotate(kv_table *table, const int32_t *preempt, int32_t n_preempt, 
 int kv_table_rotate_eager(kv_table *table, const int32_t *preempt, int32_t n_preempt, const int32_t *resume,
                           int32_t n_resume, int32_t eager_budget, int32_t *n_eager);
 
-/* The request is done: its HBM blocks and host slots are free again.  If
- * transfers the table enqueued are still in flight the call first waits for
- * them (they may be reading these blocks), so it can block the host; it does
- * not close the interval kv_last_stats() reports. */
+/* The request is done: its HBM blocks and host slots are free again.  If a
+ * transfer that names HBM blocks of this request (an eager copy, its
+ * resumption) may still be in flight, the call first waits for the engine's
+ * transfers, so it can block the host; finishing a request whose blocks no
+ * transfer has named since the engine was last idle never waits.  It does not
+ * close the interval kv_last_stats() reports. */
 int kv_table_finish(kv_table *table, int32_t req);
 
 /* Mapping of a request: per block HBM id (-1 if none), host slot (-1 if

@@ -1076,6 +1076,7 @@ int dkv::drain(kv_engine *e)
     if (e->sticky != KV_OK) return e->sticky;
     if (e->out_pending) HIPTRY(e, hipStreamSynchronize(e->s_out));
     if (e->in_pending) HIPTRY(e, hipStreamSynchronize(e->s_in));
+    e->idle_epoch++;
     return KV_OK;
 }
 
@@ -1262,6 +1263,7 @@ int kv_wait(kv_engine *e)
     e->out_pending = e->in_pending = false;
     e->out_dirty = e->in_dirty = false;
     e->hazards.join();
+    e->idle_epoch++;
     for (int k = 0; k < kRing; k++) e->ring_out_rec[k] = e->ring_in_rec[k] = false;
     if (e->batch_open) {
         e->acc.ms_e2e = now_ms() - e->t0;
@@ -1297,6 +1299,7 @@ int kv_query(kv_engine *e)
     // nothing runs any more, so nothing can race with what comes next
     e->out_dirty = e->in_dirty = false;
     e->hazards.join();
+    e->idle_epoch++;
     return KV_OK;
 }
 

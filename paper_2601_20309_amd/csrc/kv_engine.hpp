@@ -119,6 +119,10 @@ struct kv_engine {
     bool out_dirty = false;                        // stream_out holds work stream_in has not joined
     bool in_after_out = false;                     // block table in use: in-only work waits for earlier out work
     int n_tables = 0;                              // block tables attached (kv_destroy refuses while any is)
+    // Goes up every time the engine has seen all of its enqueued work finished
+    // (kv_wait, kv_query answering KV_OK, dkv::drain): what was enqueued under an
+    // earlier value is done.
+    uint64_t idle_epoch = 0;
     double t0 = 0;
     kv_stats acc{}, last{};
     int sticky = KV_OK;

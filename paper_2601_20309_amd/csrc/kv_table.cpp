@@ -18,6 +18,9 @@ struct TableReq {
     bool used = false, resident = false;
     int32_t len = 0;
     int32_t n_full = 0;  // blocks in state FULL (filled, copy to DRAM not yet issued)
+    // the engine's idle_epoch when a transfer last named HBM blocks of this request
+    // (an eager copy that reads them, a resumption that writes them); -1: never
+    int64_t named_at = -1;
     std::vector<int32_t> hbm, slot, state;
 };
 
@@ -279,6 +282,7 @@ int kv_table_eager(kv_table *t, int32_t budget, int32_t *n_done)
             return rc;
         }
         mark_synced(t, picked, 0);
+        for (const auto &pk : picked) t->req[(size_t)pk.first].named_at = (int64_t)t->e->idle_epoch;
     }
     t->cnt.copied_eager += (int64_t)t->oi.size();
     if (n_done) *n_done = (int32_t)t->oi.size();
@@ -402,6 +406,10 @@ static int rotate_impl(kv_table *t, const int32_t *pre, int32_t n_pre, const int
     const int rc = kv_rotate(t->e, t->oi.data(), t->os.data(), (int32_t)t->oi.size(), t->ii.data(), t->is.data(),
                              (int32_t)t->ii.size());
     end_undo(t, rc == KV_OK);
+    if (rc == KV_OK) {
+        for (int32_t i = 0; i < n_res; i++) t->req[(size_t)res[i]].named_at = (int64_t)t->e->idle_epoch;
+        for (const auto &pk : picked) t->req[(size_t)pk.first].named_at = (int64_t)t->e->idle_epoch;
+    }
     if (n_eager) *n_eager = rc == KV_OK ? (int32_t)picked.size() : 0;
     return rc;
 }
@@ -421,11 +429,17 @@ int kv_table_rotate_eager(kv_table *t, const int32_t *pre, int32_t n_pre, const 
 int kv_table_finish(kv_table *t, int32_t rq)
 {
     if (!t || rq < 0 || rq >= t->max_req || !t->req[(size_t)rq].used) return KV_EINVAL;
-    // its blocks and slots go to new owners, who write them at once: transfers
-    // that still read them (an eager copy, a preemption) have to be done first
-    const int rc = dkv::drain(t->e);
-    if (rc != KV_OK) return rc;
+    // Its HBM blocks go to new owners, who write them at once: a transfer that
+    // still reads or writes them (an eager copy, its resumption) has to be done
+    // first.  That can only be one enqueued since the engine was last seen idle.
+    // (Host slots need no wait: only the engine's own, ordered transfers touch them.)
     TableReq &r = t->req[(size_t)rq];
+    if (r.resident && r.named_at == (int64_t)t->e->idle_epoch) {
+        const int rc = dkv::drain(t->e);
+        if (rc != KV_OK) return rc;
+    } else if (t->e->sticky != KV_OK) {
+        return t->e->sticky;
+    }
     for (size_t b = 0; b < r.hbm.size(); b++) {
         if (r.hbm[b] >= 0) t->free_hbm.push(r.hbm[b]);
         if (r.slot[b] >= 0) t->free_slot.push(r.slot[b]);

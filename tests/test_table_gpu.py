@@ -286,3 +286,35 @@ def test_eager_copies_ride_in_the_rotation_transfer():
     assert st["bytes_out"] == 32 * blk and st["bytes_in"] == 42 * blk
     assert s.gt.kv_table_blocks(4)["states"][:31] == [O.SYNCED] * 30 + [O.FULL]
     s.close()
+
+
+def test_finish_waits_only_for_transfers_on_its_own_blocks():
+    """An eager copy of ~0.5 GiB is in flight (request 0's 256 full blocks).  Finishing
+    request 2, none of whose blocks the copy names, returns while it still runs;
+    finishing request 0 returns only when it is done."""
+    sh = W.KVShape(32, 8, 128, 16, n_hbm_blocks=400, n_host_slots=400)     # 2 MiB blocks
+    dev = torch.empty(V.n_cache_elems(sh), dtype=torch.int16, device="cuda").random_()
+    torch.cuda.synchronize()
+    eng = B.Engine(B.make_config(sh), dev.data_ptr())
+    tab = B.Table(eng, 4)
+    P = sh.block_size
+    assert tab.kv_table_append(0, 256 * P)[0] == 0
+    assert tab.kv_table_append(1, 2 * P)[0] == 0
+    assert tab.kv_table_append(2, P // 2)[0] == 0            # a partly filled block: nothing to copy
+    assert tab.kv_table_eager(256) == (0, 256)               # request 0 only
+    assert eng.kv_query() == B.KV_EBUSY, "the copy was done before the call returned"
+    assert tab.kv_table_finish(2) == 0
+    assert eng.kv_query() == B.KV_EBUSY, "finishing an uninvolved request waited for the copy"
+    assert tab.kv_table_finish(0) == 0
+    assert eng.kv_query() == 0, "request 0's blocks were freed while their copy still ran"
+    # the copies are what the cache held
+    got = tab.kv_table_blocks(1)
+    assert got["len"] == 2 * P
+    assert eng.kv_wait() == 0
+    assert eng.kv_last_stats()["bytes_out"] == 256 * (2 << 20)
+    assert tab.kv_table_eager(10) == (0, 2)                  # request 1, afterwards
+    assert tab.kv_table_finish(1) == 0                       # its copy may be in flight: waits
+    assert eng.kv_query() == 0
+    assert tab.kv_table_get_counts()["free_hbm_blocks"] == 400
+    tab.kv_table_destroy()
+    eng.kv_destroy()
