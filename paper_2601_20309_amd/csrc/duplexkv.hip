@@ -360,8 +360,9 @@ LinkShape link_shape(const kv_engine *e, LinkKind kind)
 template <bool UNPACK>
 void launch_stage(int vec, hipStream_t s, const dkv::StageParams &p, const int32_t *ids)
 {
-    const uint32_t waves_per_wg = dkv::kThreads / dkv::kWave;
-    dim3 g((p.tiles + waves_per_wg - 1) / waves_per_wg), b(dkv::kThreads);
+    // four waves to a workgroup for the gather, one for the scatter (see kv_stage_kernel)
+    const uint32_t waves_per_wg = UNPACK ? 1u : dkv::kThreads / dkv::kWave;
+    dim3 g((p.tiles + waves_per_wg - 1) / waves_per_wg), b(waves_per_wg * dkv::kWave);
 #define DKV_STAGE(V) hipLaunchKernelGGL((dkv::kv_stage_kernel<V, UNPACK>), g, b, 0, s, p, ids)
     switch (vec) {
     case 16: DKV_STAGE(dkv::u32x4); break;
