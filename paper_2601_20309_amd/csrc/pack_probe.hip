@@ -264,10 +264,16 @@ int main()
     run("pack, one 1 KiB tile per wave, non-temporal loads and stores (the library's shape)", "65536 x 256", 1,
         [&] { FIXED(1, true, true, false, 65536, 256); });
     run("pack, one 1 KiB tile per wave, plain loads and stores", "65536 x 256", 1, [&] { FIXED(1, false, false, false, 65536, 256); });
+    // the same waves, more or fewer to a workgroup
+    run("pack, one 1 KiB tile per wave, one wave per workgroup", "262144 x 64", 1, [&] { FIXED(1, true, true, false, 262144, 64); });
+    run("pack, one 1 KiB tile per wave, 16 waves per workgroup", "16384 x 1024", 1, [&] { FIXED(1, true, true, false, 16384, 1024); });
     run("unpack, waves loop over 4 KiB tiles, plain loads and stores", "2048 x 256", 0, [&] { FIXED(4, false, false, true, 2048, 256); });
     run("unpack, waves loop over 4 KiB tiles, non-temporal loads and stores", "2048 x 256", 0, [&] { FIXED(4, true, true, true, 2048, 256); });
     run("unpack, one 1 KiB tile per wave, non-temporal stores", "65536 x 256", 0, [&] { FIXED(1, false, true, true, 65536, 256); });
-    run("unpack, one 1 KiB tile per wave, non-temporal loads and stores (the library's shape)", "65536 x 256", 0,
+    run("unpack, one 1 KiB tile per wave, non-temporal loads and stores", "65536 x 256", 0,
         [&] { FIXED(1, true, true, true, 65536, 256); });
+    run("unpack, one 1 KiB tile per wave, 16 waves per workgroup", "16384 x 1024", 0, [&] { FIXED(1, true, true, true, 16384, 1024); });
+    run("unpack, one 1 KiB tile per wave, one wave per workgroup (the library's shape)", "262144 x 64", 0,
+        [&] { FIXED(1, true, true, true, 262144, 64); });
     return 0;
 }
